@@ -1,0 +1,126 @@
+"""CPU oracle for the pre-attention expert predictor.  TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes/NumPy wrapper over ``paep_oracle.c`` (plain C, double-precision
+accumulation, full sort).  Only the tests, the smoke check and the benchmark's
+CPU-baseline leg may import this package; the product path never does, and this
+package imports nothing from the product.
+
+``build()`` compiles the C file with gcc (OpenMP over tokens) into
+``oracle/libpaep_oracle.so``; ``lib()`` loads it, building it first if absent.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "paep_oracle.c")
+_SO = os.path.join(_HERE, "libpaep_oracle.so")
+_lib = None
+
+ACT_NONE, ACT_SILU, ACT_GELU = 0, 1, 2
+
+
+def build(force: bool = True) -> str:
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-fno-fast-math", _SRC, "-o", _SO, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _SO
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        build(force=False)
+        L = ctypes.CDLL(_SO)
+        c_i, c_p = ctypes.c_int, ctypes.c_void_p
+        L.paep_oracle_predict.argtypes = [c_i] * 7 + [c_p] * 8
+        L.paep_oracle_predict.restype = c_i
+        L.paep_oracle_group.argtypes = [c_p, c_i, c_i] + [c_p] * 6
+        L.paep_oracle_group.restype = c_i
+        L.paep_oracle_score.argtypes = [c_p, c_i, c_p, c_i, c_i, c_i, c_p]
+        L.paep_oracle_score.restype = c_i
+        L.paep_oracle_num_threads.restype = c_i
+        L.paep_oracle_round_bf16.argtypes = [ctypes.c_double]
+        L.paep_oracle_round_bf16.restype = ctypes.c_double
+        _lib = L
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().paep_oracle_num_threads())
+
+
+def round_bf16(v: float) -> float:
+    return float(lib().paep_oracle_round_bf16(float(v)))
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def predict(x, W1, W2, k: int, *, b1=None, b2=None, act: int = ACT_NONE,
+            round_h: bool = False, want_logits: bool = True
+            ) -> Tuple[np.ndarray, np.ndarray, Optional[np.ndarray]]:
+    """One layer: x[T,d], W1[r,d], W2[E,r] -> idx[T,k] int32, probs[T,k] f32, logits[T,E] f64."""
+    x, W1, W2 = _f32(x), _f32(W1), _f32(W2)
+    T, d = x.shape
+    r, d1 = W1.shape
+    E, r1 = W2.shape
+    if d1 != d or r1 != r:
+        raise ValueError("shape mismatch between x, W1, W2")
+    b1 = None if b1 is None else _f32(b1)
+    b2 = None if b2 is None else _f32(b2)
+    if b1 is not None and b1.shape != (r,):
+        raise ValueError("b1 must be [r]")
+    if b2 is not None and b2.shape != (E,):
+        raise ValueError("b2 must be [E]")
+    idx = np.empty((T, k), dtype=np.int32)
+    probs = np.empty((T, k), dtype=np.float32)
+    logits = np.empty((T, E), dtype=np.float64) if want_logits else None
+    rc = lib().paep_oracle_predict(T, d, r, E, k, int(act), int(bool(round_h)),
+                                   _ptr(x), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(b2),
+                                   _ptr(idx), _ptr(probs), _ptr(logits))
+    if rc != 0:
+        raise ValueError("paep_oracle_predict rejected its arguments")
+    return idx, probs, logits
+
+
+def group_by_expert(idx, E: int):
+    """idx[...] int32 (flattened) -> counts[E], offsets[E+1], token_pos[n], active[E], n_active, n_invalid."""
+    flat = np.ascontiguousarray(idx, dtype=np.int32).reshape(-1)
+    n = flat.size
+    counts = np.empty(E, dtype=np.int32)
+    offsets = np.empty(E + 1, dtype=np.int32)
+    token_pos = np.empty(n, dtype=np.int32)
+    active = np.empty(E, dtype=np.int32)
+    n_active = np.zeros(1, dtype=np.int32)
+    n_invalid = np.zeros(1, dtype=np.int32)
+    rc = lib().paep_oracle_group(_ptr(flat), n, E, _ptr(counts), _ptr(offsets), _ptr(token_pos),
+                                 _ptr(active), _ptr(n_active), _ptr(n_invalid))
+    if rc != 0:
+        raise ValueError("paep_oracle_group rejected its arguments")
+    return counts, offsets, token_pos, active, int(n_active[0]), int(n_invalid[0])
+
+
+def score(idx, ref, E: int) -> np.ndarray:
+    """idx[T,k_pred], ref[T,k_ref] -> int64[4] = (n_exact, n_hit, n_cover, n_top1)."""
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    ref = np.ascontiguousarray(ref, dtype=np.int32)
+    if idx.ndim != 2 or ref.ndim != 2 or idx.shape[0] != ref.shape[0]:
+        raise ValueError("idx and ref must be [T,k_pred] and [T,k_ref]")
+    out = np.zeros(4, dtype=np.int64)
+    rc = lib().paep_oracle_score(_ptr(idx), idx.shape[1], _ptr(ref), ref.shape[1],
+                                 idx.shape[0], E, _ptr(out))
+    if rc != 0:
+        raise ValueError("paep_oracle_score rejected its arguments")
+    return out
