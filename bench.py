@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the pre-attention expert-prediction path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input shaped
+like a paper workload: predict for all L layers (one launch set), then
+group_by_expert and score for all layers.  Inputs are resident in HBM before
+the timed region; weights rotate over several independently generated banks so
+that a step never finds its weights in the 256 MB Infinity Cache.
+
+Prints ONE JSON line: throughput in predicted tokens*layers per second, the
+roofline of the dominant kernel (measured live with HIP events around the
+predict launches of the timed steps), and the CPU oracle timed on a bounded
+sample of the same workload (a baseline, not a target).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--T tokens] [--no-cpu] [--sweep]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
+MALL_BYTES = 256 << 20
+
+
+def algorithmic_work(w, T):
+    """Per layer call: flops and bytes the method itself must do/move
+    (two weight matrices, x in, idx + probs out; h and the scores stay on chip)."""
+    flops = 2.0 * w.r * (w.d + w.E) * T
+    wbytes = 2.0 * w.r * (w.d + w.E)
+    nbytes = wbytes + 2.0 * T * w.d + 8.0 * T * w.k + (2.0 * w.E if w.zipf_bias else 0.0)
+    return flops, nbytes
+
+
+class Runner:
+    """Device buffers for one workload at one token count, and the step."""
+
+    def __init__(self, w, T, n_banks=None, seed_layers=None):
+        import numpy as np
+        import torch
+        from paper_2511_10676_amd import binding as B
+        from paper_2511_10676_amd import datagen
+        self.B, self.torch, self.w, self.T = B, torch, w, T
+        L = w.L
+        bank_bytes = 2 * L * w.r * (w.d + w.E)
+        if n_banks is None:
+            n_banks = max(2, -(-2 * MALL_BYTES // bank_bytes) + 1)
+        self.n_banks = n_banks
+        to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(torch.bfloat16).cuda()
+        t0 = time.time()
+        xs, refs, b2s = [], [], []
+        self.W1, self.W2 = [], []
+        W1_0, W2_0 = [], []
+        for l in range(L):
+            W1_0.append(datagen.make_w1(w, l)); W2_0.append(datagen.make_w2(w, l))
+            x = datagen.make_x(w, l, T)
+            b2 = datagen.make_b2(w, l)
+            Wg = datagen.make_router(w, l, W1_0[-1], W2_0[-1])
+            refs.append(datagen.router_labels(Wg, x, b2, w.k))
+            xs.append(x)
+            if b2 is not None:
+                b2s.append(b2)
+        self.x = to_dev(np.stack(xs))
+        self.ref = torch.from_numpy(np.stack(refs)).cuda()
+        self.b2 = to_dev(np.stack(b2s)) if b2s else None
+        self.W1.append(to_dev(np.stack(W1_0))); self.W2.append(to_dev(np.stack(W2_0)))
+        del xs, W1_0, W2_0
+        for bank in range(1, n_banks):
+            self.W1.append(to_dev(np.stack([datagen.make_w1(w, l, bank) for l in range(L)])))
+            self.W2.append(to_dev(np.stack([datagen.make_w2(w, l, bank) for l in range(L)])))
+        self.setup_s = time.time() - t0
+        dev = self.x.device
+        desc = B.make_desc(T, w.d, w.r, w.E, w.k, L, B.BF16)
+        self.path = B.resolve_path(desc)
+        ws = B.predict_workspace_bytes(desc)
+        self.ws = torch.empty(max(ws, 16), dtype=torch.uint8, device=dev)
+        self.out = B.Prediction(torch.empty((L, T, w.k), dtype=torch.int32, device=dev),
+                                torch.empty((L, T, w.k), dtype=torch.float32, device=dev), None, self.path)
+        self.grp = B.alloc_grouping(L, T, w.k, w.E, dev)
+        self.gws = torch.empty(max(B.group_workspace_bytes(L, T, w.k, w.E), 16), dtype=torch.uint8, device=dev)
+        self.counters = torch.empty((L, 4), dtype=torch.int64, device=dev)
+        self.i = 0
+
+    def step(self, ev=None):
+        B, w = self.B, self.w
+        bank = self.i % self.n_banks
+        self.i += 1
+        if ev is not None:
+            ev[0].record()
+        B.predict(self.x, self.W1[bank], self.W2[bank], w.k, b2=self.b2, out=self.out, workspace=self.ws)
+        if ev is not None:
+            ev[1].record()
+        B.group_by_expert(self.out.idx, w.E, out=self.grp, workspace=self.gws)
+        B.score(self.out.idx, self.ref, w.E, out=self.counters)
+
+    def timed(self, steps, warmup):
+        torch = self.torch
+        for _ in range(warmup):
+            self.step()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(steps):
+            self.step(evs[s])
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        predict_ms = sum(a.elapsed_time(b) for a, b in evs) / steps
+        return wall / steps * 1e3, predict_ms
+
+    def report(self, steps, warmup):
+        w, T = self.w, self.T
+        ms_step, predict_ms = self.timed(steps, warmup)
+        flops, nbytes = algorithmic_work(w, T)
+        if self.path == "prefill":
+            ach = flops * w.L / (predict_ms * 1e-3) / 1e12
+            roof = {"bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                    "kernel": "prefill_kernel", "kernel_ms": round(predict_ms, 4)}
+        else:
+            ach = nbytes * w.L / (predict_ms * 1e-3) / 1e9
+            roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                    "kernel": "decode_partial_kernel+decode_finalize_kernel", "kernel_ms": round(predict_ms, 4)}
+        return {"T": T, "path": self.path, "ms_per_step": round(ms_step, 4),
+                "value": round(T * w.L / (ms_step * 1e-3), 1), "roofline": roof,
+                "score_layer0": self.counters[0].cpu().numpy().tolist(), "weight_banks": self.n_banks}
+
+
+def cpu_baseline(w, T, budget_s=20.0):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    import oracle
+    from paper_2511_10676_amd import datagen
+    mac_per_token = w.r * (w.d + w.E)
+    est_rate = 0.7e9 * oracle.num_threads()                 # MAC/s guess used only to size the sample
+    tokens = int(max(1, min(T * w.L, budget_s * est_rate / mac_per_token)))
+    layers = max(1, min(w.L, tokens // T)) if T <= tokens else 1
+    Ts = min(T, tokens // layers)
+    inputs = [datagen.make_layer(w, l, Ts) for l in range(layers)]
+    t0 = time.perf_counter()
+    for lay in inputs:
+        idx, probs, _ = oracle.predict(lay.x, lay.W1, lay.W2, w.k, b2=lay.b2, want_logits=False)
+        oracle.group_by_expert(idx, w.E)
+        oracle.score(idx, lay.ref, w.E)
+    dt = time.perf_counter() - t0
+    return {"value": round(layers * Ts / dt, 1), "unit": "tokens*layers/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": round(dt, 2),
+            "sample": f"layers 0..{layers - 1} of {w.L}, first {Ts} of {T} tokens each: predict + group + score"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="deepseek_v2_lite")
+    ap.add_argument("--T", type=int, default=0, help="tokens per layer (default: the workload's prefill size)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--sweep", action="store_true", help="also time the workload's other token counts")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this library runs on one GPU; --gpus must be 1 (the path shards by tokens or layers "
+                 "with no communication in predict; see DESIGN.md)")
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    from paper_2511_10676_amd import configs
+    w = configs.get(args.workload)
+    if w.dtype != "bf16":
+        sys.exit("bench.py: choose a bf16 workload")
+    T = args.T or w.prefill_T[0]
+    run = Runner(w, T)
+    main_rep = run.report(args.steps, args.warmup)
+    line = {
+        "metric": "predicted tokens*layers per second",
+        "value": main_rep["value"], "unit": "tokens*layers/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_rep["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}-shaped: L={w.L} d={w.d} r={w.r} E={w.E} k={w.k}, T={T} tokens/layer "
+                               f"({main_rep['path']} path), step = predict + group_by_expert + score, all layers",
+                   "weight_banks": main_rep["weight_banks"], "score_layer0": main_rep["score_layer0"]},
+        "roofline": main_rep["roofline"],
+    }
+    del run
+    torch.cuda.empty_cache()
+    if args.sweep:
+        also = []
+        for T2 in list(w.decode_T) + [t for t in w.prefill_T if t != T]:
+            r2 = Runner(w, T2)
+            rep = r2.report(max(args.steps, 50) if T2 <= 64 else args.steps, args.warmup)
+            rep.pop("score_layer0")
+            also.append(rep)
+            del r2
+            torch.cuda.empty_cache()
+        line["also"] = also
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(w, T)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,174 @@
+/*
+ * paep -- pre-attention expert prediction for Mixture-of-Experts models,
+ * C ABI of the MI355X (gfx950) library.
+ *
+ * The paper ("Pre-Attention Expert Prediction and Prefetching for
+ * Mixture-of-Experts Large Language Models") attaches to every MoE layer a
+ * small predictor that reads the hidden state X entering the layer's attention
+ * block and names the experts the layer's router will pick, so that they can
+ * be prefetched while attention runs (sections 4.1-4.2).  This library is the
+ * data-parallel part of that: the predictor itself for many tokens and layers
+ * at once, the per-expert grouping of its selections (the prefetch list), and
+ * the accuracy counters of section 5.1.
+ *
+ * Conventions for every entry point
+ *   - Pointers named *_dev are DEVICE pointers owned by the caller (inputs,
+ *     outputs and workspace alike); the library allocates nothing, frees
+ *     nothing and keeps no pointer after it returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All work is enqueued on it; nothing synchronises.  Outputs are valid
+ *     once the caller has synchronised the stream.
+ *   - All arrays are dense, row-major, with the strides stated.
+ *   - Every argument check runs on the host before the first HIP call and
+ *     returns a status code; no entry point throws, aborts or prints.
+ *     A failed launch returns PAEP_ERR_HIP.
+ *   - Results are deterministic: the same inputs give the same bytes.
+ *   - Zero tokens (T = 0) is valid and produces empty / all-zero outputs.
+ */
+#ifndef PAEP_H
+#define PAEP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PAEP_OK = 0,
+    PAEP_ERR_NULL = 1,        /* a required pointer is NULL */
+    PAEP_ERR_SHAPE = 2,       /* a size is out of range or violates a divisibility rule */
+    PAEP_ERR_K = 3,           /* k outside 1..min(E, PAEP_MAX_K) */
+    PAEP_ERR_DTYPE = 4,       /* unknown dtype or activation */
+    PAEP_ERR_ALIGN = 5,       /* a pointer or stride breaks the 16-byte alignment rule */
+    PAEP_ERR_WORKSPACE = 6,   /* workspace NULL or smaller than the *_workspace_bytes answer */
+    PAEP_ERR_HIP = 7,         /* the HIP runtime reported an error */
+    PAEP_ERR_UNSUPPORTED = 8  /* the forced path cannot run this shape */
+} paep_status;
+
+typedef enum { PAEP_F32 = 0, PAEP_BF16 = 1 } paep_dtype;
+
+/* Element-wise function between the two linear layers (section 4.3):
+ * NONE is the plain two-linear predictor of the abstract and section 1,
+ * SILU is "Architecture 2", GELU (exact, erf) is "Architecture 1" at
+ * inference time with its BatchNorm folded into W1 and b1 by the caller. */
+typedef enum { PAEP_ACT_NONE = 0, PAEP_ACT_SILU = 1, PAEP_ACT_GELU = 2 } paep_act;
+
+/* Kernel family.  AUTO picks by shape; the others force one and fail with
+ * PAEP_ERR_UNSUPPORTED when the shape does not fit it. */
+typedef enum {
+    PAEP_PATH_AUTO = 0,
+    PAEP_PATH_SIMPLE = 1,     /* any dtype and shape; plain vector arithmetic */
+    PAEP_PATH_DECODE = 2,     /* bf16, T <= 64: weight-streaming, r split over workgroups */
+    PAEP_PATH_PREFILL = 3     /* bf16, large T: fused back-to-back matrix-core tiles */
+} paep_path;
+
+#define PAEP_MAX_K 32
+#define PAEP_MAX_E 1024
+
+/*
+ * Shape of one predict call.  L layers are processed in one call; layer l
+ * reads x + l*x_layer_stride, W1 + l*w1_layer_stride, W2 + l*w2_layer_stride
+ * (strides in ELEMENTS; x_layer_stride = 0 feeds the same tokens to every
+ * layer; the weight strides must be >= the matrix size, or 0 to share).
+ */
+typedef struct {
+    int32_t T;          /* tokens per layer, >= 0 */
+    int32_t d;          /* hidden size, multiple of 8 */
+    int32_t r;          /* predictor inner width, multiple of 8 */
+    int32_t E;          /* experts, 1..PAEP_MAX_E */
+    int32_t k;          /* experts to select, 1..min(E, PAEP_MAX_K) */
+    int32_t L;          /* layers in this call, >= 1 */
+    int32_t dtype;      /* paep_dtype of x, W1, W2, b1, b2 */
+    int32_t act;        /* paep_act */
+    int32_t path;       /* paep_path */
+    int32_t reserved;   /* must be 0 */
+    int64_t x_layer_stride;
+    int64_t w1_layer_stride;
+    int64_t w2_layer_stride;
+} paep_predict_desc;
+
+/* Bytes of device workspace paep_predict needs for this shape (0 is possible).
+ * Returns 0 for an invalid descriptor; paep_predict reports the reason. */
+size_t paep_predict_workspace_bytes(const paep_predict_desc *desc);
+
+/* Which kernel family AUTO resolves to for this shape (a paep_path value),
+ * or -1 for an invalid descriptor.  Host only. */
+int paep_predict_resolve_path(const paep_predict_desc *desc);
+
+/*
+ * The predictor (paper eq. 3-4 with f = two linear layers, section 4.3;
+ * softmax as in eq. 1).  For every layer l and token t:
+ *     h = W1_l x_t (+ b1_l);   in bf16 storage h is rounded to bf16;  h = act(h)
+ *     s = W2_l h   (+ b2_l)                      scores, fp32
+ *     idx[l,t,:]   = the k experts with the highest s, in descending score
+ *                    order, equal scores by ascending expert id
+ *     probs[l,t,j] = softmax(s)[idx[l,t,j]]      over all E scores
+ * Selection is done on the raw scores: softmax preserves ranking
+ * (sections 1 and 3.1).  h and s never go to memory unless logits_dev is
+ * given.
+ *
+ *   x_dev   [L or 1][T, d]   W1_dev [L][r, d]   W2_dev [L][E, r]
+ *   b1_dev  [L][r] or NULL   b2_dev [L][E] or NULL   (dense, layer stride r / E)
+ *   idx_dev [L][T, k] int32  probs_dev [L][T, k] float
+ *   logits_dev [L][T, E] float or NULL: the scores s, for checking only
+ *   workspace_dev: at least paep_predict_workspace_bytes(desc) bytes,
+ *                  16-byte aligned; may be NULL when that is 0.
+ * x, W1, W2 and their layer strides must be 16-byte aligned.
+ * Inputs must be finite; a NaN score orders below every number.
+ */
+paep_status paep_predict(const paep_predict_desc *desc,
+                         const void *x_dev, const void *W1_dev, const void *W2_dev,
+                         const void *b1_dev, const void *b2_dev,
+                         int32_t *idx_dev, float *probs_dev, float *logits_dev,
+                         void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/* Workspace bytes for paep_group_by_expert. */
+size_t paep_group_workspace_bytes(int32_t L, int32_t T, int32_t k, int32_t E);
+
+/*
+ * Per-expert grouping of the selections, i.e. the prefetch list of the paper's
+ * workflow (section 4.2, third stage: the selected experts drive prefetching).
+ * For every layer l, over the n = T*k flat positions p = t*k + j of idx[l]:
+ *     counts[l,e]     number of positions with idx = e
+ *     offsets[l,0..E] exclusive prefix sum of counts; offsets[l,E] = number
+ *                     of valid positions
+ *     token_pos[l, offsets[l,e] .. offsets[l,e+1]) = the positions p with
+ *                     idx = e in ascending p (token = p / k, slot = p % k);
+ *                     entries past offsets[l,E] are -1
+ *     active[l, 0..n_active[l]) = the experts with counts > 0, ascending id
+ *                     (the experts to prefetch); the rest of the row is -1
+ *     n_invalid[l]    positions whose id is outside [0, E): they are skipped
+ * All outputs int32.  Requires T*k < 2^31 / 2 and E <= PAEP_MAX_E.
+ */
+paep_status paep_group_by_expert(const int32_t *idx_dev, int32_t L, int32_t T, int32_t k, int32_t E,
+                                 int32_t *counts_dev, int32_t *offsets_dev, int32_t *token_pos_dev,
+                                 int32_t *active_dev, int32_t *n_active_dev, int32_t *n_invalid_dev,
+                                 void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/*
+ * Accuracy counters of section 5.1 (and the deployment scenarios at the end
+ * of section 4.1).  For every layer l and token t let P = set(idx[l,t,:k_pred])
+ * and R = set(ref[l,t,:k_ref]); then
+ *     counters[l,0] += (P == R)          exact match
+ *     counters[l,1] += |P & R|           correctly predicted experts
+ *     counters[l,2] += (R subset of P)   hit under over-provisioning (k_pred > k_ref)
+ *     counters[l,3] += (idx[l,t,0] in R) top-1
+ * A row holding an id outside [0, E) in either array adds nothing.
+ * counters_dev is [L, 4] int64 and is overwritten (not accumulated into).
+ */
+paep_status paep_score(const int32_t *idx_dev, int32_t k_pred,
+                       const int32_t *ref_dev, int32_t k_ref,
+                       int32_t L, int32_t T, int32_t E,
+                       long long *counters_dev, void *stream);
+
+const char *paep_status_string(paep_status s);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int paep_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PAEP_H */

@@ -1,0 +1,255 @@
+"""Python binding of the C-ABI library declared in ``include/paep.h``.
+
+Argument marshalling only: tensors (PyTorch-ROCm, used for device memory and
+streams and nothing else) are checked, their device pointers and the current
+HIP stream are handed to the C entry points of the same names, and a non-zero
+status becomes an exception.  There is no fallback: if ``libpaep.so`` has not
+been built (``python -m paper_2511_10676_amd.build``), loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import NamedTuple, Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpaep.so")
+
+# enums of paep.h
+F32, BF16 = 0, 1
+ACT = {"none": 0, "silu": 1, "gelu": 2}
+PATH = {"auto": 0, "simple": 1, "decode": 2, "prefill": 3}
+PATH_NAME = {v: k for k, v in PATH.items()}
+MAX_K, MAX_E = 32, 1024
+
+STATUS_NAMES = ["PAEP_OK", "PAEP_ERR_NULL", "PAEP_ERR_SHAPE", "PAEP_ERR_K", "PAEP_ERR_DTYPE",
+                "PAEP_ERR_ALIGN", "PAEP_ERR_WORKSPACE", "PAEP_ERR_HIP", "PAEP_ERR_UNSUPPORTED"]
+
+EXPORTS = ["paep_predict_workspace_bytes", "paep_predict_resolve_path", "paep_predict",
+           "paep_group_workspace_bytes", "paep_group_by_expert", "paep_score",
+           "paep_status_string", "paep_version"]
+
+
+class PredictDesc(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int32), ("d", ctypes.c_int32), ("r", ctypes.c_int32),
+                ("E", ctypes.c_int32), ("k", ctypes.c_int32), ("L", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("act", ctypes.c_int32), ("path", ctypes.c_int32),
+                ("reserved", ctypes.c_int32),
+                ("x_layer_stride", ctypes.c_int64), ("w1_layer_stride", ctypes.c_int64),
+                ("w2_layer_stride", ctypes.c_int64)]
+
+
+class PaepError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        name = STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else str(status)
+        try:
+            msg = lib().paep_status_string(status).decode()
+        except Exception:  # pragma: no cover
+            msg = ""
+        super().__init__(f"{where}: {name} ({msg})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C library.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2511_10676_amd.build` "
+                "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        dp = ctypes.POINTER(PredictDesc)
+        L.paep_predict_workspace_bytes.argtypes = [dp]
+        L.paep_predict_workspace_bytes.restype = sz
+        L.paep_predict_resolve_path.argtypes = [dp]
+        L.paep_predict_resolve_path.restype = ctypes.c_int
+        L.paep_predict.argtypes = [dp] + [vp] * 9 + [sz, vp]
+        L.paep_predict.restype = ctypes.c_int
+        L.paep_group_workspace_bytes.argtypes = [i32] * 4
+        L.paep_group_workspace_bytes.restype = sz
+        L.paep_group_by_expert.argtypes = [vp] + [i32] * 4 + [vp] * 7 + [sz, vp]
+        L.paep_group_by_expert.restype = ctypes.c_int
+        L.paep_score.argtypes = [vp, i32, vp, i32, i32, i32, i32, vp, vp]
+        L.paep_score.restype = ctypes.c_int
+        L.paep_status_string.argtypes = [ctypes.c_int]
+        L.paep_status_string.restype = ctypes.c_char_p
+        L.paep_version.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _storage_dtype(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported storage dtype {t.dtype}; use float32 or bfloat16")
+
+
+def _need_device(*tensors):
+    for t in tensors:
+        if t is not None and (not t.is_cuda or not t.is_contiguous()):
+            raise ValueError("every tensor must be a contiguous device tensor")
+
+
+class Prediction(NamedTuple):
+    idx: torch.Tensor                 # [L, T, k] int32
+    probs: torch.Tensor               # [L, T, k] float32
+    logits: Optional[torch.Tensor]    # [L, T, E] float32 or None
+    path: str
+
+
+def make_desc(T, d, r, E, k, L, dtype, act="none", path="auto",
+              x_layer_stride=None, w1_layer_stride=None, w2_layer_stride=None) -> PredictDesc:
+    return PredictDesc(T=T, d=d, r=r, E=E, k=k, L=L, dtype=dtype, act=ACT[act], path=PATH[path], reserved=0,
+                       x_layer_stride=T * d if x_layer_stride is None else x_layer_stride,
+                       w1_layer_stride=r * d if w1_layer_stride is None else w1_layer_stride,
+                       w2_layer_stride=E * r if w2_layer_stride is None else w2_layer_stride)
+
+
+def predict_workspace_bytes(desc: PredictDesc) -> int:
+    return int(lib().paep_predict_workspace_bytes(ctypes.byref(desc)))
+
+
+def resolve_path(desc: PredictDesc) -> str:
+    p = int(lib().paep_predict_resolve_path(ctypes.byref(desc)))
+    return PATH_NAME.get(p, "invalid")
+
+
+def predict(x: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, k: int, *,
+            b1: Optional[torch.Tensor] = None, b2: Optional[torch.Tensor] = None,
+            act: str = "none", path: str = "auto", want_logits: bool = False,
+            out: Optional[Prediction] = None, workspace: Optional[torch.Tensor] = None,
+            stream=None) -> Prediction:
+    """predict(x[L|1,T,d], W1[L,r,d], W2[L,E,r], k) -> idx[L,T,k], probs[L,T,k].
+
+    2-D inputs are taken as one layer.  x with a leading dimension of 1 (or
+    2-D x with 3-D weights) feeds the same tokens to every layer.  `out` and
+    `workspace` let a caller reuse buffers; otherwise they are allocated here.
+    """
+    if W1.dim() == 2:
+        W1 = W1.unsqueeze(0)
+    if W2.dim() == 2:
+        W2 = W2.unsqueeze(0)
+    if x.dim() == 2:
+        x = x.unsqueeze(0)
+    _need_device(x, W1, W2, b1, b2)
+    L, r, d = W1.shape
+    L2, E, r2 = W2.shape
+    Lx, T, dx = x.shape
+    if L2 != L or r2 != r or dx != d or Lx not in (1, L):
+        raise ValueError(f"shape mismatch: x{tuple(x.shape)} W1{tuple(W1.shape)} W2{tuple(W2.shape)}")
+    dt = _storage_dtype(x)
+    if _storage_dtype(W1) != dt or _storage_dtype(W2) != dt:
+        raise TypeError("x, W1 and W2 must share one storage dtype")
+    for b, n in ((b1, r), (b2, E)):
+        if b is not None and (b.numel() != L * n or _storage_dtype(b) != dt):
+            raise ValueError("bias must be [L, r] / [L, E] in the storage dtype")
+    desc = make_desc(T, d, r, E, k, L, dt, act, path, x_layer_stride=(T * d if Lx == L and L > 1 else 0))
+    if L == 1:
+        desc.x_layer_stride = T * d
+    dev = x.device
+    if out is None:
+        idx = torch.empty((L, T, k), dtype=torch.int32, device=dev)
+        probs = torch.empty((L, T, k), dtype=torch.float32, device=dev)
+        logits = torch.empty((L, T, E), dtype=torch.float32, device=dev) if want_logits else None
+    else:
+        idx, probs, logits = out.idx, out.probs, out.logits
+        _need_device(idx, probs, logits)
+        if tuple(idx.shape) != (L, T, k) or tuple(probs.shape) != (L, T, k) or idx.dtype != torch.int32 \
+                or probs.dtype != torch.float32:
+            raise ValueError("out buffers have the wrong shape or dtype")
+        if logits is not None and (tuple(logits.shape) != (L, T, E) or logits.dtype != torch.float32):
+            raise ValueError("logits buffer has the wrong shape or dtype")
+    need = predict_workspace_bytes(desc)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib().paep_predict(ctypes.byref(desc), _ptr(x), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(b2),
+                            _ptr(idx), _ptr(probs), _ptr(logits), _ptr(workspace), ws_bytes,
+                            _stream_ptr(stream))
+    if st != 0:
+        raise PaepError(st, "paep_predict")
+    return Prediction(idx, probs, logits, resolve_path(desc))
+
+
+class Grouping(NamedTuple):
+    counts: torch.Tensor      # [L, E] int32
+    offsets: torch.Tensor     # [L, E+1] int32
+    token_pos: torch.Tensor   # [L, T*k] int32
+    active: torch.Tensor      # [L, E] int32
+    n_active: torch.Tensor    # [L] int32
+    n_invalid: torch.Tensor   # [L] int32
+
+
+def group_workspace_bytes(L: int, T: int, k: int, E: int) -> int:
+    return int(lib().paep_group_workspace_bytes(L, T, k, E))
+
+
+def alloc_grouping(L: int, T: int, k: int, E: int, device) -> Grouping:
+    i32 = dict(dtype=torch.int32, device=device)
+    return Grouping(torch.empty((L, E), **i32), torch.empty((L, E + 1), **i32),
+                    torch.empty((L, T * k), **i32), torch.empty((L, E), **i32),
+                    torch.empty((L,), **i32), torch.empty((L,), **i32))
+
+
+def group_by_expert(idx: torch.Tensor, E: int, *, out: Optional[Grouping] = None,
+                    workspace: Optional[torch.Tensor] = None, stream=None) -> Grouping:
+    """group_by_expert(idx[L,T,k]) -> counts[L,E], offsets[L,E+1], token lists, prefetch list."""
+    if idx.dim() == 2:
+        idx = idx.unsqueeze(0)
+    _need_device(idx)
+    if idx.dtype != torch.int32 or idx.dim() != 3:
+        raise TypeError("idx must be int32 [L, T, k]")
+    L, T, k = idx.shape
+    if out is None:
+        out = alloc_grouping(L, T, k, E, idx.device)
+    need = group_workspace_bytes(L, T, k, E)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=idx.device)
+    st = lib().paep_group_by_expert(_ptr(idx), L, T, k, E, _ptr(out.counts), _ptr(out.offsets),
+                                    _ptr(out.token_pos), _ptr(out.active), _ptr(out.n_active),
+                                    _ptr(out.n_invalid), _ptr(workspace),
+                                    workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if st != 0:
+        raise PaepError(st, "paep_group_by_expert")
+    return out
+
+
+def score(idx: torch.Tensor, ref_idx: torch.Tensor, E: int, *, out: Optional[torch.Tensor] = None,
+          stream=None) -> torch.Tensor:
+    """score(idx[L,T,k_pred], ref_idx[L,T,k_ref]) -> int64 [L,4]: n_exact, n_hit, n_cover, n_top1."""
+    if idx.dim() == 2:
+        idx = idx.unsqueeze(0)
+    if ref_idx.dim() == 2:
+        ref_idx = ref_idx.unsqueeze(0)
+    _need_device(idx, ref_idx)
+    if idx.dtype != torch.int32 or ref_idx.dtype != torch.int32:
+        raise TypeError("idx and ref_idx must be int32")
+    L, T, k_pred = idx.shape
+    if ref_idx.shape[0] != L or ref_idx.shape[1] != T:
+        raise ValueError("idx and ref_idx must agree on [L, T]")
+    k_ref = ref_idx.shape[2]
+    if out is None:
+        out = torch.empty((L, 4), dtype=torch.int64, device=idx.device)
+    st = lib().paep_score(_ptr(idx), k_pred, _ptr(ref_idx), k_ref, L, T, E, _ptr(out), _stream_ptr(stream))
+    if st != 0:
+        raise PaepError(st, "paep_score")
+    return out

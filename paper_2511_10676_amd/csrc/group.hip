@@ -1,0 +1,207 @@
+// Per-expert grouping of the selected expert ids: histogram, device-wide
+// exclusive scan, stable index compaction (a counting sort by expert id).
+// This produces the prefetch list that the paper's workflow (section 4.2,
+// third stage) derives from the selection: which experts are needed and which
+// tokens need each of them.
+//
+// Three launches, all layers of a call batched on gridDim.y:
+//   hist     every wave owns WAVE_ITEMS consecutive flat positions and counts
+//            them per expert in its own LDS histogram, then stores that
+//            histogram row to the workspace: hist[layer][wave_chunk][E + 1]
+//            (slot E counts ids outside [0, E)).
+//   scan     one workgroup per layer turns each expert's column of that
+//            matrix into running sums (the base of every chunk inside the
+//            expert's group), yielding counts; a block scan over experts gives
+//            offsets; a second scan compacts the non-empty experts into the
+//            active list.
+//   scatter  every wave revisits its positions in order, 64 at a time: lanes
+//            holding the same expert find each other with ballots over the id
+//            bits, take consecutive slots from the wave's LDS cursor for that
+//            expert, and write their position.  Order inside a group is
+//            ascending position because chunks, batches and lanes are all
+//            visited in ascending order.
+#include "paep_internal.h"
+
+namespace paep {
+
+static constexpr int GROUP_THREADS = 256;
+static constexpr int GROUP_WAVES = GROUP_THREADS / 64;
+static constexpr int WAVE_ITEMS = 1024;                 // positions per wave
+static constexpr int BLOCK_ITEMS = WAVE_ITEMS * GROUP_WAVES;
+static constexpr int MAX_E = 1024;
+
+static inline int wave_chunks(long long n) { return (int)((n + WAVE_ITEMS - 1) / WAVE_ITEMS); }
+static inline int block_chunks(long long n) { return (int)((n + BLOCK_ITEMS - 1) / BLOCK_ITEMS); }
+
+__global__ __launch_bounds__(GROUP_THREADS) void group_hist_kernel(
+    const int32_t* __restrict__ idx, int n, int E, int nwc, int32_t* __restrict__ hist)
+{
+    __shared__ int32_t lh[GROUP_WAVES][MAX_E + 1];
+    const int layer = blockIdx.y, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int e = lane; e <= E; e += 64) lh[wave][e] = 0;
+    __syncthreads();
+    const int wc = blockIdx.x * GROUP_WAVES + wave;
+    const long long base = (long long)wc * WAVE_ITEMS;
+    const int32_t* src = idx + (long long)layer * n;
+    for (int i = lane; i < WAVE_ITEMS; i += 64) {
+        const long long p = base + i;
+        if (p < n) {
+            const int32_t e = src[p];
+            atomicAdd(&lh[wave][(e >= 0 && e < E) ? e : E], 1);
+        }
+    }
+    __syncthreads();
+    if (wc < nwc) {
+        int32_t* dst = hist + ((long long)layer * nwc + wc) * (E + 1);
+        for (int e = lane; e <= E; e += 64) dst[e] = lh[wave][e];
+    }
+}
+
+// exclusive scan of one int per thread over the 256-thread block
+__device__ __forceinline__ int block_exclusive_scan(int v, int* total, int* buf)
+{
+    const int tid = threadIdx.x;
+    buf[tid] = v;
+    __syncthreads();
+    for (int off = 1; off < GROUP_THREADS; off <<= 1) {
+        const int add = (tid >= off) ? buf[tid - off] : 0;
+        __syncthreads();
+        buf[tid] += add;
+        __syncthreads();
+    }
+    const int incl = buf[tid];
+    *total = buf[GROUP_THREADS - 1];
+    __syncthreads();
+    return incl - v;
+}
+
+__global__ __launch_bounds__(GROUP_THREADS) void group_scan_kernel(
+    int E, int nwc, int32_t* __restrict__ hist, int32_t* __restrict__ counts,
+    int32_t* __restrict__ offsets, int32_t* __restrict__ active, int32_t* __restrict__ n_active,
+    int32_t* __restrict__ n_invalid)
+{
+    __shared__ int buf[GROUP_THREADS];
+    const int layer = blockIdx.x, tid = threadIdx.x;
+    int32_t* h = hist + (long long)layer * nwc * (E + 1);
+    // thread owns experts e = tid*per .. tid*per + per - 1 (consecutive, so that
+    // the block scan over threads is a scan over experts)
+    const int per = (E + GROUP_THREADS - 1) / GROUP_THREADS;   // <= 4
+    int cnt[MAX_E / GROUP_THREADS];
+    int mine = 0, mine_active = 0;
+#pragma unroll
+    for (int q = 0; q < MAX_E / GROUP_THREADS; ++q) {
+        cnt[q] = 0;
+        const int e = tid * per + q;
+        if (q < per && e < E) {
+            int run = 0;
+            for (int wc = 0; wc < nwc; ++wc) {
+                const int c = h[(long long)wc * (E + 1) + e];
+                h[(long long)wc * (E + 1) + e] = run;       // chunk's base inside the group
+                run += c;
+            }
+            cnt[q] = run;
+            counts[(long long)layer * E + e] = run;
+            mine += run;
+            mine_active += (run > 0);
+        }
+    }
+    int total, total_active;
+    int off = block_exclusive_scan(mine, &total, buf);
+    int aoff = block_exclusive_scan(mine_active, &total_active, buf);
+    int32_t* offs = offsets + (long long)layer * (E + 1);
+    int32_t* act = active + (long long)layer * E;
+#pragma unroll
+    for (int q = 0; q < MAX_E / GROUP_THREADS; ++q) {
+        const int e = tid * per + q;
+        if (q < per && e < E) {
+            offs[e] = off;
+            off += cnt[q];
+            if (cnt[q] > 0) act[aoff++] = e;
+        }
+    }
+    if (tid == 0) {
+        offs[E] = total;
+        n_active[layer] = total_active;
+    }
+    for (int i = total_active + tid; i < E; i += GROUP_THREADS) act[i] = -1;
+    // ids outside [0, E)
+    int bad = 0;
+    for (int wc = tid; wc < nwc; wc += GROUP_THREADS) bad += h[(long long)wc * (E + 1) + E];
+    int bad_total;
+    (void)block_exclusive_scan(bad, &bad_total, buf);
+    if (tid == 0) n_invalid[layer] = bad_total;
+}
+
+__global__ __launch_bounds__(GROUP_THREADS) void group_scatter_kernel(
+    const int32_t* __restrict__ idx, int n, int E, int nbits, int nwc,
+    const int32_t* __restrict__ base, const int32_t* __restrict__ offsets,
+    int32_t* __restrict__ token_pos)
+{
+    __shared__ int32_t cursor[GROUP_WAVES][MAX_E];
+    const int layer = blockIdx.y, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wc = blockIdx.x * GROUP_WAVES + wave;
+    const int32_t* offs = offsets + (long long)layer * (E + 1);
+    if (wc < nwc) {
+        const int32_t* b = base + ((long long)layer * nwc + wc) * (E + 1);
+        for (int e = lane; e < E; e += 64) cursor[wave][e] = offs[e] + b[e];
+    }
+    const int total = offs[E];
+    __syncthreads();
+    const int32_t* src = idx + (long long)layer * n;
+    int32_t* dst = token_pos + (long long)layer * n;
+    const long long first = (long long)wc * WAVE_ITEMS;
+    for (int i = 0; i < WAVE_ITEMS; i += 64) {
+        const long long p = first + i + lane;
+        int32_t e = -1;
+        if (p < n) e = src[p];
+        const bool valid = (e >= 0 && e < E);
+        // lanes with the same expert id
+        uint64_t same = __ballot(valid);
+        for (int b = 0; b < nbits; ++b) {
+            const bool bit = (e >> b) & 1;
+            const uint64_t set = __ballot(valid && bit);
+            same &= bit ? set : ~set;
+        }
+        int slot = 0;
+        if (valid) {
+            const int before = __popcll(same & ((1ull << lane) - 1ull));
+            slot = cursor[wave][e] + before;
+            dst[slot] = (int32_t)p;
+        }
+        __syncthreads();
+        if (valid && lane == 63 - __clzll((long long)same)) cursor[wave][e] += __popcll(same);
+        __syncthreads();
+        // the unused tail of token_pos
+        if (p < n && p >= total) dst[p] = -1;
+    }
+}
+
+size_t group_workspace_bytes(int L, int T, int k, int E)
+{
+    const long long n = (long long)T * k;
+    const long long nwc = wave_chunks(n) > 0 ? wave_chunks(n) : 1;
+    return sizeof(int32_t) * (size_t)L * (size_t)nwc * (size_t)(E + 1);
+}
+
+hipError_t launch_group(const int32_t* idx, int L, int T, int k, int E,
+                        int32_t* counts, int32_t* offsets, int32_t* token_pos,
+                        int32_t* active, int32_t* n_active, int32_t* n_invalid,
+                        void* workspace, hipStream_t stream)
+{
+    const int n = T * k;
+    const int nwc = wave_chunks(n);
+    const int nbc = block_chunks(n);
+    int nbits = 0;
+    while ((1 << nbits) < E) ++nbits;
+    int32_t* hist = (int32_t*)workspace;
+    if (nbc > 0)
+        hipLaunchKernelGGL(group_hist_kernel, dim3(nbc, L), dim3(GROUP_THREADS), 0, stream, idx, n, E, nwc, hist);
+    hipLaunchKernelGGL(group_scan_kernel, dim3(L), dim3(GROUP_THREADS), 0, stream, E, nwc, hist, counts,
+                       offsets, active, n_active, n_invalid);
+    if (nbc > 0)
+        hipLaunchKernelGGL(group_scatter_kernel, dim3(nbc, L), dim3(GROUP_THREADS), 0, stream, idx, n, E,
+                           nbits, nwc, hist, offsets, token_pos);
+    return hipGetLastError();
+}
+
+}  // namespace paep

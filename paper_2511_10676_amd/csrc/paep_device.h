@@ -1,0 +1,156 @@
+// Device-side building blocks shared by the predict kernels (gfx950, wave64).
+//
+//  * bf16 <-> fp32 conversions on raw bit patterns,
+//  * order-preserving packing of (score, expert id) into one 64-bit key, so
+//    that an unsigned compare implements "higher score first, equal scores by
+//    lower expert id" (the tie rule of the C header),
+//  * a sorted top-K list kept in registers, filled by streaming over a row of
+//    scores and merged across the lanes that share a row with wave shuffles,
+//  * the softmax (eq. 1 of the paper) gathered at the selected experts.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace paep {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) short short4v;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round-to-nearest-even; inputs are finite in this library
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float round_to_bf16(float f) { return bf16_bits_to_f32(f32_to_bf16_bits(f)); }
+
+// two floats -> packed pair of bf16 (lo in bits 0..15)
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    return (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
+}
+
+__device__ __forceinline__ float apply_act(float v, int act)
+{
+    if (act == 1) return v / (1.0f + __expf(-v));                        // SiLU
+    if (act == 2) return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f));  // exact GELU
+    return v;
+}
+
+// ---------------------------------------------------------------------------
+// (score, expert) -> 64-bit key.  Larger key = better candidate.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t orderable(float f)
+{
+    f += 0.0f;                                   // -0 -> +0 so the two zeros tie
+    uint32_t u = __float_as_uint(f);
+    if (f != f) return 0u;                       // NaN orders below -inf
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ float unorderable(uint32_t o)
+{
+    uint32_t u = (o & 0x80000000u) ? (o & 0x7FFFFFFFu) : ~o;
+    return __uint_as_float(u);
+}
+
+__device__ __forceinline__ uint64_t make_key(float score, int e)
+{
+    return ((uint64_t)orderable(score) << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)e);
+}
+__device__ __forceinline__ int key_expert(uint64_t key) { return (int)(0xFFFFFFFFu - (uint32_t)key); }
+__device__ __forceinline__ float key_score(uint64_t key) { return unorderable((uint32_t)(key >> 32)); }
+
+// Sorted (descending) list of the KMAX best keys seen; 0 marks an empty slot
+// (every real key is > 0 because its low word is >= 0xFFFFFFFF - PAEP_MAX_E).
+template <int KMAX>
+struct TopList {
+    uint64_t key[KMAX];
+
+    __device__ __forceinline__ void clear()
+    {
+#pragma unroll
+        for (int j = 0; j < KMAX; ++j) key[j] = 0;
+    }
+    __device__ __forceinline__ void insert(uint64_t c)
+    {
+#pragma unroll
+        for (int j = 0; j < KMAX; ++j) {
+            const bool gt = c > key[j];
+            const uint64_t hi = gt ? c : key[j];
+            c = gt ? key[j] : c;
+            key[j] = hi;
+        }
+    }
+};
+
+// Softmax + top-k of one row of E scores held in LDS, computed by G
+// consecutive lanes (G a power of two, the group aligned to G).  Lane g of
+// the group scans e = g, g+G, ...; the per-lane lists are merged with
+// xor-shuffles so that every lane ends with the row's list; lane g writes
+// outputs j = g, g+G, ... < k.
+template <int KMAX, int G>
+__device__ __forceinline__ void row_softmax_topk(const float* zrow, int E, int k, int g,
+                                                 int32_t* idx_row, float* probs_row)
+{
+    TopList<KMAX> top;
+    top.clear();
+    for (int e = g; e < E; e += G) top.insert(make_key(zrow[e], e));
+#pragma unroll
+    for (int mask = 1; mask < G; mask <<= 1) {
+        uint64_t other[KMAX];
+#pragma unroll
+        for (int j = 0; j < KMAX; ++j) other[j] = __shfl_xor((unsigned long long)top.key[j], mask, 64);
+#pragma unroll
+        for (int j = 0; j < KMAX; ++j) top.insert(other[j]);
+    }
+    const float m = key_score(top.key[0]);       // row maximum (NaNs order last)
+    float s = 0.0f;
+    for (int e = g; e < E; e += G) {
+        const float v = zrow[e];
+        if (v == v) s += __expf(v - m);
+    }
+#pragma unroll
+    for (int mask = 1; mask < G; mask <<= 1) s += __shfl_xor(s, mask, 64);
+    const float inv = 1.0f / s;
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j) {
+        if (j < k && (j % G) == g) {
+            idx_row[j] = key_expert(top.key[j]);
+            probs_row[j] = __expf(key_score(top.key[j]) - m) * inv;
+        }
+    }
+}
+
+// Dispatch on the smallest list length that holds k.
+template <int G>
+__device__ __forceinline__ void row_softmax_topk_any(const float* zrow, int E, int k, int g,
+                                                     int32_t* idx_row, float* probs_row)
+{
+    if (k <= 2)       row_softmax_topk<2, G>(zrow, E, k, g, idx_row, probs_row);
+    else if (k <= 8)  row_softmax_topk<8, G>(zrow, E, k, g, idx_row, probs_row);
+    else if (k <= 16) row_softmax_topk<16, G>(zrow, E, k, g, idx_row, probs_row);
+    else              row_softmax_topk<32, G>(zrow, E, k, g, idx_row, probs_row);
+}
+
+// Same, for kernels that only accept k <= 16 (keeps their register budget small).
+template <int G>
+__device__ __forceinline__ void row_softmax_topk_upto16(const float* zrow, int E, int k, int g,
+                                                        int32_t* idx_row, float* probs_row)
+{
+    if (k <= 2)      row_softmax_topk<2, G>(zrow, E, k, g, idx_row, probs_row);
+    else if (k <= 8) row_softmax_topk<8, G>(zrow, E, k, g, idx_row, probs_row);
+    else             row_softmax_topk<16, G>(zrow, E, k, g, idx_row, probs_row);
+}
+
+}  // namespace paep

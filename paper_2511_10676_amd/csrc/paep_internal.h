@@ -1,0 +1,49 @@
+// Host-side launcher prototypes shared between the C-ABI layer and the kernel
+// translation units.  Every launcher assumes its arguments were validated by
+// the C-ABI layer and returns the hipError_t of its launches.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace paep {
+
+struct PredictArgs {
+    int T, d, r, E, k, L, dtype, act;
+    long long x_stride, w1_stride, w2_stride;   // elements
+    const void* x;
+    const void* W1;
+    const void* W2;
+    const void* b1;
+    const void* b2;
+    int32_t* idx;
+    float* probs;
+    float* logits;      // nullable
+    void* workspace;
+    hipStream_t stream;
+};
+
+// plain vector-ALU kernel, any dtype / shape
+bool simple_supported(const PredictArgs& a);
+hipError_t launch_predict_simple(const PredictArgs& a);
+
+// bf16 weight-streaming kernel for T <= 64
+bool decode_supported(const PredictArgs& a);
+size_t decode_workspace_bytes(const PredictArgs& a);
+hipError_t launch_predict_decode(const PredictArgs& a);
+
+// bf16 fused matrix-core kernel for large T
+bool prefill_supported(const PredictArgs& a);
+hipError_t launch_predict_prefill(const PredictArgs& a);
+
+size_t group_workspace_bytes(int L, int T, int k, int E);
+hipError_t launch_group(const int32_t* idx, int L, int T, int k, int E,
+                        int32_t* counts, int32_t* offsets, int32_t* token_pos,
+                        int32_t* active, int32_t* n_active, int32_t* n_invalid,
+                        void* workspace, hipStream_t stream);
+
+hipError_t launch_score(const int32_t* idx, int k_pred, const int32_t* ref, int k_ref,
+                        int L, int T, int E, long long* counters, hipStream_t stream);
+
+}  // namespace paep

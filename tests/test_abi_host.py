@@ -1,0 +1,132 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol the header declares, and rejects bad arguments before any HIP
+call (the pointers used here are never dereferenced)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2511_10676_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, E_NULL, E_SHAPE, E_K, E_DTYPE, E_ALIGN, E_WS, E_HIP, E_UNSUP = range(9)
+FAKE = ctypes.c_void_p(0x10000)          # aligned, never touched: every case fails validation or is empty
+ODD = ctypes.c_void_p(0x10008)
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "paep.h")).read()
+    declared = set(re.findall(r"\b(paep_[a-z_]+)\s*\(", hdr))
+    assert declared == set(B.EXPORTS)
+    lib = B.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.paep_version() >= 100
+    assert lib.paep_status_string(0) == b"ok"
+    for s in range(1, 9):
+        assert len(lib.paep_status_string(s)) > 3
+
+
+def _predict(desc, x=FAKE, W1=FAKE, W2=FAKE, idx=FAKE, probs=FAKE, ws=None, ws_bytes=0):
+    d = ctypes.byref(desc) if desc is not None else None
+    return B.lib().paep_predict(d, x, W1, W2, None, None, idx, probs, None, ws, ws_bytes, None)
+
+
+def _desc(**kw):
+    base = dict(T=0, d=256, r=64, E=16, k=2, L=1, dtype=B.F32)
+    base.update(kw)
+    return B.make_desc(**base)
+
+
+def test_predict_rejects_bad_descriptors():
+    assert _predict(None) == E_NULL
+    assert _predict(_desc(dtype=7)) == E_DTYPE
+    bad_act = _desc()
+    bad_act.act = 9
+    assert _predict(bad_act) == E_DTYPE
+    bad_path = _desc()
+    bad_path.path = 9
+    assert _predict(bad_path) == E_UNSUP
+    res = _desc()
+    res.reserved = 1
+    assert _predict(res) == E_SHAPE
+    for kw in (dict(T=-1), dict(L=0), dict(d=260), dict(d=0), dict(r=12), dict(E=0), dict(E=1025)):
+        assert _predict(_desc(**kw)) == E_SHAPE, kw
+    for kw in (dict(k=0), dict(k=17), dict(E=64, k=33)):
+        assert _predict(_desc(**kw)) == E_K, kw
+    assert _predict(_desc(T=8, L=2, x_layer_stride=8 * 256 - 8)) == E_SHAPE
+    assert _predict(_desc(T=8, L=2, w1_layer_stride=64 * 256 + 4)) == E_ALIGN
+    assert _predict(_desc(T=8, L=2, w2_layer_stride=-8)) == E_SHAPE
+
+
+def test_predict_rejects_bad_pointers_and_paths():
+    assert _predict(_desc(), x=None) == E_NULL
+    assert _predict(_desc(), idx=None) == E_NULL
+    assert _predict(_desc(), W1=ODD) == E_ALIGN
+    assert _predict(_desc(path="prefill")) == E_UNSUP          # fp32 storage has no matrix-core path
+    assert _predict(_desc(path="decode")) == E_UNSUP
+    big = _desc(dtype=B.BF16, d=2048, r=2048, E=64, k=6, L=26, T=8)
+    need = B.predict_workspace_bytes(big)
+    assert need == 4 * 26 * (2048 // 64) * 8 * 64
+    assert _predict(big, ws=None, ws_bytes=0) == E_WS
+    assert _predict(big, ws=FAKE, ws_bytes=need - 1) == E_WS
+    assert _predict(big, ws=ODD, ws_bytes=need) == E_WS
+
+
+def test_empty_call_is_valid_and_touches_nothing():
+    assert _predict(_desc(T=0)) == OK
+    assert _predict(_desc(T=0, dtype=B.BF16, d=2048, r=2048, E=64, k=6, L=26)) == OK
+
+
+def test_path_resolution_by_shape():
+    ds = dict(dtype=B.BF16, d=2048, r=2048, E=64, k=6, L=26)
+    assert B.resolve_path(_desc(T=1, **ds)) == "decode"
+    assert B.resolve_path(_desc(T=64, **ds)) == "decode"
+    assert B.resolve_path(_desc(T=65, **ds)) == "prefill"
+    assert B.resolve_path(_desc(T=4096, **ds)) == "prefill"
+    assert B.resolve_path(_desc(T=512)) == "simple"
+    assert B.resolve_path(_desc(T=4096, dtype=B.BF16, d=72, r=40, E=13, k=5)) == "simple"
+    assert B.resolve_path(_desc(T=4096, dtype=B.BF16, d=2048, r=4096, E=256, k=8)) == "prefill"
+    assert B.resolve_path(_desc(k=0)) == "invalid"
+    assert B.predict_workspace_bytes(_desc(T=4096, **ds)) == 0
+    assert B.predict_workspace_bytes(_desc(k=0)) == 0
+
+
+def _group(idx=FAKE, L=1, T=0, k=2, E=16, outs=(FAKE,) * 6, ws=FAKE, ws_bytes=1 << 20):
+    return B.lib().paep_group_by_expert(idx, L, T, k, E, *outs, ws, ws_bytes, None)
+
+
+def test_group_rejects_bad_arguments():
+    assert _group(L=0) == E_SHAPE
+    assert _group(T=-1) == E_SHAPE
+    assert _group(E=0) == E_SHAPE
+    assert _group(E=1025) == E_SHAPE
+    assert _group(k=0) == E_K
+    assert _group(k=33) == E_K
+    assert _group(T=1 << 29, k=2) == E_SHAPE
+    assert _group(outs=(None,) + (FAKE,) * 5) == E_NULL
+    assert _group(T=4, idx=None) == E_NULL
+    assert _group(T=4, ws=None) == E_WS
+    assert _group(T=4096, k=8, E=256, ws_bytes=16) == E_WS
+    assert B.group_workspace_bytes(1, 4096, 8, 256) == 4 * 32 * 257
+    assert B.group_workspace_bytes(3, 0, 8, 256) == 4 * 3 * 257
+    assert B.group_workspace_bytes(0, 1, 1, 1) == 0
+
+
+def test_score_rejects_bad_arguments():
+    f = B.lib().paep_score
+    assert f(FAKE, 2, FAKE, 2, 0, 4, 16, FAKE, None) == E_SHAPE
+    assert f(FAKE, 2, FAKE, 2, 1, -4, 16, FAKE, None) == E_SHAPE
+    assert f(FAKE, 2, FAKE, 2, 1, 4, 2000, FAKE, None) == E_SHAPE
+    assert f(FAKE, 0, FAKE, 2, 1, 4, 16, FAKE, None) == E_K
+    assert f(FAKE, 2, FAKE, 40, 1, 4, 16, FAKE, None) == E_K
+    assert f(FAKE, 2, FAKE, 2, 1, 4, 16, None, None) == E_NULL
+    assert f(None, 2, FAKE, 2, 1, 4, 16, FAKE, None) == E_NULL
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libpaep.so")
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        B.lib()

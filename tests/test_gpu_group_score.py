@@ -1,0 +1,120 @@
+"""GPU parity of paep_group_by_expert and paep_score with the CPU oracle:
+integer work, compared bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_10676_amd import binding as B
+from paper_2511_10676_amd import configs, datagen
+
+pytestmark = pytest.mark.gpu
+
+
+def _skewed_idx(g, L, T, k, E, zipf=1.2):
+    """Per-token k distinct experts, popularity ~ Zipf (the Gumbel top-k trick)."""
+    logp = -zipf * np.log(np.arange(1, E + 1))
+    out = np.empty((L, T, k), dtype=np.int32)
+    for l in range(L):
+        perm = g.permutation(E)
+        keys = logp[None, :] + g.gumbel(size=(T, E))
+        out[l] = perm[np.argsort(-keys, axis=1)[:, :k]]
+    return out
+
+
+def _check_group(idx, E):
+    L, T, k = idx.shape
+    got = B.group_by_expert(torch.from_numpy(idx).cuda(), E)
+    torch.cuda.synchronize()
+    for l in range(L):
+        counts, offsets, pos, active, n_active, n_invalid = oracle.group_by_expert(idx[l], E)
+        assert np.array_equal(got.counts[l].cpu().numpy(), counts), f"counts layer {l}"
+        assert np.array_equal(got.offsets[l].cpu().numpy(), offsets), f"offsets layer {l}"
+        assert np.array_equal(got.token_pos[l].cpu().numpy(), pos), f"token_pos layer {l}"
+        assert np.array_equal(got.active[l].cpu().numpy(), active), f"active layer {l}"
+        assert int(got.n_active[l]) == n_active and int(got.n_invalid[l]) == n_invalid
+    return got
+
+
+@pytest.mark.parametrize("T,k,E,L", [
+    (1, 1, 1, 1), (0, 6, 64, 2), (1, 6, 64, 3), (9, 7, 64, 1), (64, 1, 16, 2), (65, 1, 16, 2),
+    (171, 6, 64, 2), (1024, 1, 2, 1), (1025, 1, 300, 1), (4096, 6, 64, 3), (8192, 8, 128, 2),
+    (8192, 2, 16, 2), (32768, 8, 256, 1), (700, 3, 1000, 2),
+])
+def test_group_matches_oracle(T, k, E, L):
+    g = np.random.default_rng(T * 31 + k * 7 + E)
+    idx = _skewed_idx(g, L, T, min(k, E), E) if T > 0 else np.zeros((L, 0, k), dtype=np.int32)
+    _check_group(idx, E)
+
+
+def test_group_with_invalid_ids_and_repeats():
+    g = np.random.default_rng(5)
+    idx = g.integers(-3, 70, size=(2, 3000, 6)).astype(np.int32)     # ids outside [0, 64) on purpose
+    got = _check_group(idx, 64)
+    assert int(got.n_invalid.sum()) > 0
+    one = np.full((1, 5000, 8), 7, dtype=np.int32)                  # everything lands in one group
+    _check_group(one, 128)
+
+
+def test_group_is_reproducible():
+    g = np.random.default_rng(6)
+    idx = torch.from_numpy(_skewed_idx(g, 2, 5000, 8, 128)).cuda()
+    a = B.group_by_expert(idx, 128)
+    b = B.group_by_expert(idx, 128)
+    torch.cuda.synchronize()
+    for u, v in zip(a, b):
+        assert torch.equal(u, v)
+
+
+@pytest.mark.parametrize("T,kp,kr,E,L", [
+    (0, 6, 6, 64, 2), (1, 2, 2, 16, 1), (255, 6, 6, 64, 2), (257, 10, 6, 64, 3), (4096, 6, 6, 64, 2),
+    (5000, 12, 8, 128, 2), (3000, 8, 8, 256, 1), (999, 3, 2, 16, 4), (500, 32, 5, 1000, 1),
+])
+def test_score_matches_oracle(T, kp, kr, E, L):
+    g = np.random.default_rng(T + kp * 3 + E)
+    ref = _skewed_idx(g, L, T, kr, E) if T else np.zeros((L, 0, kr), np.int32)
+    idx = np.empty((L, T, kp), dtype=np.int32)
+    for l in range(L):
+        for t in range(T):
+            # mostly the label set (shuffled, padded with other experts), sometimes perturbed
+            keep = ref[l, t].copy()
+            if g.random() < 0.4:
+                keep[g.integers(kr)] = g.integers(E)
+            pool = np.setdiff1d(np.arange(E), keep)
+            row = np.concatenate([np.unique(keep), g.permutation(pool)])[:kp]
+            idx[l, t] = g.permutation(row)
+    got = B.score(torch.from_numpy(idx).cuda(), torch.from_numpy(ref).cuda(), E)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    for l in range(L):
+        want = oracle.score(idx[l], ref[l], E)
+        assert got[l].tolist() == want.tolist(), f"layer {l}"
+
+
+def test_score_hand_cases_and_invalid_rows():
+    E = 12
+    ref = np.array([[[0, 1, 2], [3, 4, 5], [6, 7, 8], [9, 10, 11], [0, 5, 10]]], dtype=np.int32)
+    idx = np.array([[[2, 1, 0], [3, 4, 11], [6, 6, 6], [12, 10, 9], [1, 2, 3]]], dtype=np.int32)
+    got = B.score(torch.from_numpy(idx).cuda(), torch.from_numpy(ref).cuda(), E).cpu().numpy()[0]
+    assert got.tolist() == oracle.score(idx[0], ref[0], E).tolist() == [1, 6, 1, 3]
+
+
+def test_toy_end_to_end_matches_oracle_and_golden():
+    import json, os
+    w = configs.get("toy")
+    lay = datagen.make_layer(w, 0, w.prefill_T[0])
+    dev = lambda a: torch.from_numpy(a).cuda()
+    out = B.predict(dev(lay.x), dev(lay.W1), dev(lay.W2), w.k)
+    grp = B.group_by_expert(out.idx, w.E)
+    sc = B.score(out.idx, dev(lay.ref)[None], w.E)
+    torch.cuda.synchronize()
+    idx_ref, probs_ref, _ = oracle.predict(lay.x, lay.W1, lay.W2, w.k)
+    # fp32 storage: the GPU selection equals the oracle's wherever the oracle's gap exceeds the tolerance;
+    # on this seed that is every row
+    assert np.array_equal(out.idx[0].cpu().numpy(), idx_ref)
+    counts, offsets, pos, active, n_active, _ = oracle.group_by_expert(idx_ref, w.E)
+    assert np.array_equal(grp.counts[0].cpu().numpy(), counts)
+    assert np.array_equal(grp.token_pos[0].cpu().numpy(), pos)
+    with open(os.path.join(os.path.dirname(__file__), "golden", "toy_oracle.json")) as f:
+        gold = json.load(f)
+    assert sc[0].cpu().numpy().tolist() == gold["score_k2_vs_ref"] == oracle.score(idx_ref, lay.ref, w.E).tolist()
