@@ -101,7 +101,8 @@ paep_status paep_predict(const paep_predict_desc* desc,
 {
     const paep_status st = check_desc(desc);
     if (st != PAEP_OK) return st;
-    if (!x_dev || !W1_dev || !W2_dev || !idx_dev || !probs_dev) return PAEP_ERR_NULL;
+    if (!W1_dev || !W2_dev) return PAEP_ERR_NULL;
+    if (desc->T > 0 && (!x_dev || !idx_dev || !probs_dev)) return PAEP_ERR_NULL;
     if (!aligned16(x_dev) || !aligned16(W1_dev) || !aligned16(W2_dev)) return PAEP_ERR_ALIGN;
     paep::PredictArgs a = to_args(desc);
     const int path = resolve(desc, a);

@@ -23,27 +23,60 @@
 
 namespace paep {
 
-static constexpr int PF_THREADS = 256;
-static constexpr int BM = 128;          // tokens per workgroup
-static constexpr int BN = 128;          // hidden units per chunk
-static constexpr int BK = 64;           // d-elements per LDS tile
-static constexpr int LDT = BK + 8;      // padded LDS row, bf16 elements
-static constexpr int STAGE_ELEMS = (BN + BM) * LDT;
-static constexpr int TILE_BYTES = 2 * STAGE_ELEMS * 2;
+// s_waitcnt immediate that waits for vmcnt <= n and nothing else (gfx9 encoding)
+#define PAEP_VMCNT(n) ((((n) & 0xF) | (((n) >> 4) << 14)) | 0x0F70)
 
-// EB32: 32-expert blocks (E <= 32 * EB32).  WR: waves along the hidden-unit
-// axis of a chunk (2: a 2 x 2 wave grid of 64 x 64 tiles; 1: four waves side by
-// side along tokens, 128 x 32 each, which halves the score accumulators per
-// wave and is what E = 256 needs to stay in registers).  OCC: workgroups per CU
-// the register budget is sized for.
-template <int EB32, int WR, int OCC>
-__global__ __launch_bounds__(PF_THREADS, OCC) void prefill_kernel(
+typedef const void __attribute__((address_space(1)))* gptr_t;
+typedef void __attribute__((address_space(3)))* lptr_t;
+
+// Tile configuration.
+//   BM tokens x BN hidden units per workgroup and chunk, BK elements of d per
+//   LDS tile, NS LDS stages; WR x WT waves over (hidden units, tokens); OCC
+//   workgroups per CU the register budget is sized for.
+// Tiles travel global -> LDS with global_load_lds_dwordx4 (no staging
+// registers), NS stages deep, so a tile is requested NS-1 iterations before it
+// is used.  An LDS tile row holds BK bf16 = CPR chunks of 16 bytes; chunk c of
+// row R sits in slot c ^ swz(R), chosen so that the 16-lane groups of a
+// ds_read_b128 touch 64 distinct banks.  The swizzle is applied on the global
+// side of the copy (a lane picks which chunk it fetches), because the LDS side
+// of that instruction is fixed to lane * 16 bytes from a wave-uniform base.
+template <int BM_, int BN_, int BK_, int NS_, int WR_, int WT_, int OCC_>
+struct PfCfg {
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, NS = NS_, WR = WR_, WT = WT_, OCC = OCC_;
+    static constexpr int NW = WR * WT, THREADS = 64 * NW;
+    static constexpr int WM = BN / WR, WN = BM / WT;        // wave tile: hidden units x tokens
+    static constexpr int MI = WM / 32, NI = WN / 32;        // 32 x 32 blocks per wave
+    static constexpr int CPR = BK / 8;                      // 16-byte chunks per tile row
+    static constexpr int RPI = 64 / CPR;                    // tile rows moved by one copy instruction
+    static constexpr int AJ = BN / RPI / NW, BJ = BM / RPI / NW;   // copy instructions per wave and tile
+    static constexpr int STAGE_ELEMS = (BN + BM) * BK;
+    static constexpr int TILE_BYTES = NS * STAGE_ELEMS * 2;
+    static_assert(BK == 32 || BK == 64, "BK");
+    static_assert(AJ >= 1 && BJ >= 1 && AJ * RPI * NW == BN && BJ * RPI * NW == BM, "copy split");
+    static_assert(MI >= 1 && NI >= 1, "wave tile");
+    static_assert((AJ + BJ) * (NS - 1) <= 48, "vmcnt budget");
+    static __device__ __forceinline__ int swz(int row) { return BK == 32 ? ((row >> 2) & 3) : ((row >> 1) & 7); }
+};
+
+// Token rows of the score tile that are staged in LDS at once (<= 128 KB).
+template <class C, int EB32>
+struct PfZRows {
+    static constexpr int value = (C::BM * (EB32 * 32 + 1) * 4 > 128 * 1024) ? C::BM / 2 : C::BM;
+};
+
+// EB32: 32-expert blocks (E <= 32 * EB32).
+template <class C, int EB32>
+__global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     int T, int d, int r, int E, int k, int act, int tiles_per_layer, int total_wgs,
     long long xs_, long long w1s, long long w2s,
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ W1, const uint16_t* __restrict__ W2,
     const uint16_t* __restrict__ b1, const uint16_t* __restrict__ b2,
     int32_t* __restrict__ idx, float* __restrict__ probs, float* __restrict__ logits)
 {
+    constexpr int BM = C::BM, BN = C::BN, BK = C::BK, NS = C::NS, WR = C::WR, WT = C::WT;
+    constexpr int WM = C::WM, WN = C::WN, MI = C::MI, NI = C::NI, CPR = C::CPR, RPI = C::RPI;
+    constexpr int AJ = C::AJ, BJ = C::BJ, STAGE_ELEMS = C::STAGE_ELEMS;
+
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     uint16_t* tiles = (uint16_t*)smem_raw;
     float* zs = (float*)smem_raw;                         // reused after the main loop
@@ -61,28 +94,30 @@ __global__ __launch_bounds__(PF_THREADS, OCC) void prefill_kernel(
     const int t0 = (wg - layer * tiles_per_layer) * BM;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    constexpr int WT = 4 / WR;                 // waves along tokens
-    constexpr int MI = BN / WR / 32;           // 32-unit blocks per wave
-    constexpr int NI = BM / WT / 32;           // 32-token blocks per wave
-    constexpr int WM = BN / WR, WN = BM / WT;  // wave tile
     const int wr = wave / WT, wt = wave % WT;
     const int l32 = lane & 31, g = lane >> 5;
     const uint16_t* xl = x + (long long)layer * xs_;
     const uint16_t* W1l = W1 + (long long)layer * w1s;
     const uint16_t* W2l = W2 + (long long)layer * w2s;
 
-    // global -> LDS copy assignment: 4 rows-of-16B per thread and operand
-    const int crow = tid >> 3, ccol = (tid & 7) * 8;      // rows crow + 32*q
-    const uint16_t* asrc[4];
-    const uint16_t* bsrc[4];
-    bool bok[4];
+    // global -> LDS copy assignment: per tile, wave w moves rows
+    // (w*AJ + j)*RPI .. +RPI of the W1 tile (j < AJ) and likewise of the token
+    // tile; lane l supplies row l / CPR, slot l % CPR of its instruction.
+    const uint16_t* asrc[AJ];
+    const uint16_t* bsrc[BJ];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int row = crow + 32 * q;
-        asrc[q] = W1l + (long long)row * d + ccol;
-        const int tok = t0 + row;
-        bok[q] = tok < T;
-        bsrc[q] = xl + (long long)(bok[q] ? tok : 0) * d + ccol;
+    for (int j = 0; j < AJ; ++j) {
+        const int row = (wave * AJ + j) * RPI + lane / CPR;
+        const int chunk = (lane % CPR) ^ C::swz(row);
+        asrc[j] = W1l + (long long)row * d + chunk * 8;
+    }
+#pragma unroll
+    for (int j = 0; j < BJ; ++j) {
+        const int row = (wave * BJ + j) * RPI + lane / CPR;
+        const int chunk = (lane % CPR) ^ C::swz(row);
+        int tok = t0 + row;
+        tok = tok < T ? tok : T - 1;                       // rows past the end re-read the last token; never stored
+        bsrc[j] = xl + (long long)tok * d + chunk * 8;
     }
 
     f32x16 acc1[MI][NI];
@@ -101,47 +136,61 @@ __global__ __launch_bounds__(PF_THREADS, OCC) void prefill_kernel(
             for (int i = 0; i < 16; ++i) acc2[eb][ni][i] = 0.f;
 
     const int NK = d / BK, NC = r / BN, NT = NK * NC;
-    u32x4 ra[4], rb[4];
 
-    auto load_tile = [&](int it) {
+    auto issue_tile = [&](int it) {
         const int kt = it % NK, n = it / NK;
+        uint16_t* As = tiles + (it % NS) * STAGE_ELEMS;
+        uint16_t* Bs = As + BN * BK;
         const long long aoff = (long long)n * BN * d + kt * BK;
         const int boff = kt * BK;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            ra[q] = *(const u32x4*)(asrc[q] + aoff);
-            rb[q] = bok[q] ? *(const u32x4*)(bsrc[q] + boff) : u32x4{0u, 0u, 0u, 0u};
-        }
-    };
-    auto store_tile = [&](int stage) {
-        uint16_t* As = tiles + stage * STAGE_ELEMS;
-        uint16_t* Bs = As + BN * LDT;
+        for (int j = 0; j < AJ; ++j)
+            __builtin_amdgcn_global_load_lds((gptr_t)(asrc[j] + aoff), (lptr_t)(As + (wave * AJ + j) * RPI * BK), 16, 0, 0);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            *(u32x4*)(As + (crow + 32 * q) * LDT + ccol) = ra[q];
-            *(u32x4*)(Bs + (crow + 32 * q) * LDT + ccol) = rb[q];
-        }
+        for (int j = 0; j < BJ; ++j)
+            __builtin_amdgcn_global_load_lds((gptr_t)(bsrc[j] + boff), (lptr_t)(Bs + (wave * BJ + j) * RPI * BK), 16, 0, 0);
     };
 
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
+    // LDS read offsets (elements) of this lane's A / B fragments per k-step
+    int aoffs[MI][BK / 16], boffs[NI][BK / 16];
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const int row = wr * WM + mi * 32 + l32;
+            aoffs[mi][ks] = row * BK + (((ks * 2 + g) ^ C::swz(row)) * 8);
+        }
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+            const int row = wt * WN + ni * 32 + l32;
+            boffs[ni][ks] = BN * BK + row * BK + (((ks * 2 + g) ^ C::swz(row)) * 8);
+        }
+    }
+
+#pragma unroll
+    for (int p = 0; p < NS - 1; ++p)
+        if (p < NT) issue_tile(p);
 
     for (int it = 0; it < NT; ++it) {
         const int kt = it % NK, n = it / NK;
-        if (it + 1 < NT) load_tile(it + 1);
+        // tile `it` has landed once at most the NS-2 younger tiles are in flight
+        if (it + NS - 2 < NT) __builtin_amdgcn_s_waitcnt(PAEP_VMCNT((AJ + BJ) * (NS - 2)));
+        else                  __builtin_amdgcn_s_waitcnt(PAEP_VMCNT(0));
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();                      // everyone's part of tile `it` is in LDS, and
+        asm volatile("" ::: "memory");                     // everyone is done reading stage (it-1) % NS
+        if (it + NS - 1 < NT) issue_tile(it + NS - 1);
         {
-            const uint16_t* As = tiles + (it & 1) * STAGE_ELEMS + (wr * WM + l32) * LDT + g * 8;
-            const uint16_t* Bs = tiles + (it & 1) * STAGE_ELEMS + BN * LDT + (wt * WN + l32) * LDT + g * 8;
+            const uint16_t* st = tiles + (it % NS) * STAGE_ELEMS;
 #pragma unroll
             for (int ks = 0; ks < BK / 16; ++ks) {
                 bf16x8 a[MI], b[NI];
 #pragma unroll
                 for (int mi = 0; mi < MI; ++mi)
-                    a[mi] = __builtin_bit_cast(bf16x8, *(const u32x4*)(As + mi * 32 * LDT + ks * 16));
+                    a[mi] = __builtin_bit_cast(bf16x8, *(const u32x4*)(st + aoffs[mi][ks]));
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni)
-                    b[ni] = __builtin_bit_cast(bf16x8, *(const u32x4*)(Bs + ni * 32 * LDT + ks * 16));
+                    b[ni] = __builtin_bit_cast(bf16x8, *(const u32x4*)(st + boffs[ni][ks]));
 #pragma unroll
                 for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -149,8 +198,6 @@ __global__ __launch_bounds__(PF_THREADS, OCC) void prefill_kernel(
                         acc1[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc1[mi][ni], 0, 0, 0);
             }
         }
-        if (it + 1 < NT) store_tile((it + 1) & 1);
-        __syncthreads();
 
         if (kt == NK - 1) {
             // chunk n of h is complete in acc1: feed it to the second layer.
@@ -208,87 +255,112 @@ __global__ __launch_bounds__(PF_THREADS, OCC) void prefill_kernel(
                     for (int i = 0; i < 16; ++i) acc1[mi][ni][i] = 0.f;
         }
     }
+    __syncthreads();                                       // all tile reads done before LDS is reused
 
     // acc2[eb][ni][i] = partial score of token wt*WN + ni*32 + l32,
     //                   expert eb*32 + 8*(i/4) + 4*g + i%4, over this wave's hidden units.
-    // Waves that share tokens add their parts through LDS, wr = 0 first.
+    // The score tile goes to LDS ZROWS tokens at a time (all of it unless E is
+    // large); waves that share tokens add their parts there, wr = 0 first.
+    constexpr int ZROWS = PfZRows<C, EB32>::value;
+    constexpr int ZG = C::THREADS / ZROWS;                 // lanes per token row in the epilogue
+    static_assert(ZROWS % WN == 0 && (ZG == 2 || ZG == 4), "epilogue split");
     const int ZP = E + 1;
+#pragma unroll 1
+    for (int zp = 0; zp < BM / ZROWS; ++zp) {
+        const bool mine = (wt * WN) / ZROWS == zp;
 #pragma unroll
-    for (int pass = 0; pass < WR; ++pass) {
-        if (wr == pass) {
+        for (int pass = 0; pass < WR; ++pass) {
+            if (mine && wr == pass) {
 #pragma unroll
-            for (int eb = 0; eb < EB32; ++eb)
+                for (int eb = 0; eb < EB32; ++eb)
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
+                    for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int e = eb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-                        const int tl = wt * WN + ni * 32 + l32;
-                        if (e < E) {
-                            float v = acc2[eb][ni][i];
-                            if (pass == 0) {
-                                if (b2) v += bf16_bits_to_f32(b2[(long long)layer * E + e]);
-                            } else {
-                                v = zs[tl * ZP + e] + v;
+                        for (int i = 0; i < 16; ++i) {
+                            const int e = eb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
+                            const int tl = wt * WN + ni * 32 + l32 - zp * ZROWS;
+                            if (e < E) {
+                                float v = acc2[eb][ni][i];
+                                if (pass == 0) {
+                                    if (b2) v += bf16_bits_to_f32(b2[(long long)layer * E + e]);
+                                } else {
+                                    v = zs[tl * ZP + e] + v;
+                                }
+                                zs[tl * ZP + e] = v;
                             }
-                            zs[tl * ZP + e] = v;
                         }
-                    }
+            }
+            __syncthreads();
+        }
+        const int tbase = t0 + zp * ZROWS;
+        if (logits) {
+            for (int i = tid; i < ZROWS * E; i += C::THREADS) {
+                const int tl = i / E, e = i - tl * E;
+                if (tbase + tl < T) logits[((long long)layer * T + tbase + tl) * E + e] = zs[tl * ZP + e];
+            }
+        }
+        {
+            const int tl = tid / ZG, gg = tid % ZG;
+            // the lanes of a group take the same branch (same token)
+            if (tbase + tl < T) {
+                const long long row = (long long)layer * T + tbase + tl;
+                row_softmax_topk_upto16<ZG>(zs + tl * ZP, E, k, gg, idx + row * k, probs + row * k);
+            }
         }
         __syncthreads();
     }
-
-    if (logits) {
-        for (int i = tid; i < BM * E; i += PF_THREADS) {
-            const int tl = i / E, e = i - tl * E;
-            if (t0 + tl < T) logits[((long long)layer * T + t0 + tl) * E + e] = zs[tl * ZP + e];
-        }
-    }
-    {
-        const int tl = tid >> 1, gg = tid & 1;
-        // both lanes of a pair take the same branch (same token)
-        if (t0 + tl < T) {
-            const long long row = (long long)layer * T + t0 + tl;
-            row_softmax_topk_upto16<2>(zs + tl * ZP, E, k, gg, idx + row * k, probs + row * k);
-        }
-    }
 }
 
-static size_t prefill_lds_bytes(int E)
+// Configurations.  Big: 256 x 256 tiles, 8 waves, one workgroup per CU -- the
+// fewest bytes per flop through the CU's vector memory path, for E <= 64.
+// Mid: 256 tokens x 128 hidden units, 8 waves side by side along tokens, which
+// keeps the score accumulators at E/2 registers per lane (E up to 256).
+// Small: 128 x 128, 4 waves, any r that is a multiple of 128 and short inputs.
+typedef PfCfg<256, 256, 32, 4, 2, 4, 1> CfgBig;
+typedef PfCfg<256, 128, 32, 4, 1, 8, 1> CfgMid;
+typedef PfCfg<128, 128, 32, 4, 2, 2, 2> CfgSmall;
+typedef PfCfg<128, 128, 32, 4, 1, 4, 1> CfgSmallWide;
+
+template <class C, int EB32>
+static size_t cfg_lds_bytes(int E)
 {
-    const size_t z = sizeof(float) * (size_t)BM * (size_t)(E + 1);
-    return z > (size_t)TILE_BYTES ? z : (size_t)TILE_BYTES;
+    const size_t z = sizeof(float) * (size_t)PfZRows<C, EB32>::value * (size_t)(E + 1);
+    return z > (size_t)C::TILE_BYTES ? z : (size_t)C::TILE_BYTES;
 }
 
 bool prefill_supported(const PredictArgs& a)
 {
-    return a.dtype == 1 && a.T >= 1 && a.d % BK == 0 && a.r % BN == 0 && a.E <= 256 && a.k <= 16 &&
-           prefill_lds_bytes(a.E) <= 160 * 1024;
+    return a.dtype == 1 && a.T >= 1 && a.d % 32 == 0 && a.r % 128 == 0 && a.E <= 256 && a.k <= 16;
 }
+
+template <class C, int EB32>
+static hipError_t launch_cfg(const PredictArgs& a)
+{
+    const int tiles = (a.T + C::BM - 1) / C::BM;
+    const int total = tiles * a.L;
+    const size_t lds = cfg_lds_bytes<C, EB32>(a.E);
+    auto kern = prefill_kernel<C, EB32>;
+    hipError_t err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(kern, dim3(total), dim3(C::THREADS), lds, a.stream, a.T, a.d, a.r, a.E, a.k, a.act, tiles,
+                       total, a.x_stride, a.w1_stride, a.w2_stride, (const uint16_t*)a.x, (const uint16_t*)a.W1,
+                       (const uint16_t*)a.W2, (const uint16_t*)a.b1, (const uint16_t*)a.b2, a.idx, a.probs,
+                       a.logits);
+    return hipGetLastError();
+}
+
+// The large tiles pay off once they fill a good part of the 256 CUs; below
+// that, more and smaller workgroups win.
+static bool enough_large_tiles(const PredictArgs& a) { return (long long)((a.T + 255) / 256) * a.L >= 128; }
 
 hipError_t launch_predict_prefill(const PredictArgs& a)
 {
-    const int tiles = (a.T + BM - 1) / BM;
-    const int total = tiles * a.L;
-    const size_t lds = prefill_lds_bytes(a.E);
-    hipError_t err;
-#define PAEP_LAUNCH_PF(EBV, WRV, OCCV)                                                               \
-    do {                                                                                             \
-        auto kern = prefill_kernel<EBV, WRV, OCCV>;                                                           \
-        err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,     \
-                                  (int)lds);                                                         \
-        if (err != hipSuccess) return err;                                                           \
-        hipLaunchKernelGGL(kern, dim3(total), dim3(PF_THREADS), lds, a.stream, a.T, a.d, a.r, a.E,   \
-                           a.k, a.act, tiles, total, a.x_stride, a.w1_stride, a.w2_stride,           \
-                           (const uint16_t*)a.x, (const uint16_t*)a.W1, (const uint16_t*)a.W2,       \
-                           (const uint16_t*)a.b1, (const uint16_t*)a.b2, a.idx, a.probs, a.logits);  \
-    } while (0)
-    if (a.E <= 32)       PAEP_LAUNCH_PF(1, 2, 2);
-    else if (a.E <= 64)  PAEP_LAUNCH_PF(2, 2, 2);
-    else if (a.E <= 128) PAEP_LAUNCH_PF(4, 2, 1);
-    else                 PAEP_LAUNCH_PF(8, 1, 1);
-#undef PAEP_LAUNCH_PF
-    return hipGetLastError();
+    const bool large = enough_large_tiles(a);
+    const bool big_ok = large && (a.r % 256 == 0);
+    if (a.E <= 32)  return big_ok ? launch_cfg<CfgBig, 1>(a) : launch_cfg<CfgSmall, 1>(a);
+    if (a.E <= 64)  return big_ok ? launch_cfg<CfgBig, 2>(a) : launch_cfg<CfgSmall, 2>(a);
+    if (a.E <= 128) return large ? launch_cfg<CfgMid, 4>(a) : launch_cfg<CfgSmallWide, 4>(a);
+    return large ? launch_cfg<CfgMid, 8>(a) : launch_cfg<CfgSmallWide, 8>(a);
 }
 
 }  // namespace paep

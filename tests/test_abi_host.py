@@ -61,8 +61,10 @@ def test_predict_rejects_bad_descriptors():
 
 
 def test_predict_rejects_bad_pointers_and_paths():
-    assert _predict(_desc(), x=None) == E_NULL
-    assert _predict(_desc(), idx=None) == E_NULL
+    assert _predict(_desc(T=8), x=None) == E_NULL
+    assert _predict(_desc(T=8), idx=None) == E_NULL
+    assert _predict(_desc(T=0), W2=None) == E_NULL
+    assert _predict(_desc(T=0), x=None, idx=None, probs=None) == OK
     assert _predict(_desc(), W1=ODD) == E_ALIGN
     assert _predict(_desc(path="prefill")) == E_UNSUP          # fp32 storage has no matrix-core path
     assert _predict(_desc(path="decode")) == E_UNSUP

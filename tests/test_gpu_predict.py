@@ -148,6 +148,15 @@ def test_empty_call():
     assert o.idx.shape == (2, 0, 6)
 
 
+@pytest.mark.parametrize("E,k,r", [(64, 6, 256), (128, 8, 128), (256, 8, 384), (24, 2, 512)])
+def test_prefill_large_tile_configs_with_ragged_tail(E, k, r):
+    """Enough tokens that the large-tile kernels are chosen, a token count that
+    is not a multiple of any tile, every row checked."""
+    x, W1, W2, b1, b2 = _rand_layers(70 + E, L=4, T=8229, d=64, r=r, E=E, dtype="bf16", bias=True)
+    out, *_ = _run_and_check(x, W1, W2, b1, b2, k, "bf16", path="prefill", what=f"prefill large tiles E={E} r={r}")
+    assert out.path == "prefill"
+
+
 # ------------------------------------------------------------------ paper-shaped, full size, sampled rows
 def _paper_shaped(name, T, layers, n_rows, path):
     w = configs.get(name)
@@ -182,7 +191,7 @@ def test_qwen3_shaped_decode(T):
 
 
 def test_qwen3_shaped_prefill_sampled():
-    _paper_shaped("qwen3_30b_a3b", 8192, [0, 47], 48, "prefill")
+    _paper_shaped("qwen3_30b_a3b", 8192, [0, 17, 30, 47], 32, "prefill")
 
 
 @pytest.mark.parametrize("T", [1, 32])
@@ -191,7 +200,7 @@ def test_phi_shaped_decode(T):
 
 
 def test_phi_shaped_prefill_sampled():
-    _paper_shaped("phi_mini_moe", 8192, [0, 31], 48, "prefill")
+    _paper_shaped("phi_mini_moe", 8192, [0, 9, 20, 31], 32, "prefill")
 
 
 def test_stress_shaped_prefill_sampled_with_near_ties():
