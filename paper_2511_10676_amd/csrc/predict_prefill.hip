@@ -18,6 +18,8 @@
 // After the last chunk the two waves that share a token range add their
 // partial scores through LDS in a fixed order, and two lanes per token run
 // the softmax/top-k epilogue.
+#include <type_traits>
+
 #include "paep_device.h"
 #include "paep_internal.h"
 
@@ -28,6 +30,15 @@ namespace paep {
 
 typedef const void __attribute__((address_space(1)))* gptr_t;
 typedef void __attribute__((address_space(3)))* lptr_t;
+
+template <int V> using IC = std::integral_constant<int, V>;
+template <int N, class F> __device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (N > 0) {
+        static_for<N - 1>(f);
+        f(IC<N - 1>{});
+    }
+}
 
 // Tile configuration.
 //   BM tokens x BN hidden units per workgroup and chunk, BK elements of d per
@@ -54,7 +65,7 @@ struct PfCfg {
     static_assert(BK == 32 || BK == 64, "BK");
     static_assert(AJ >= 1 && BJ >= 1 && AJ * RPI * NW == BN && BJ * RPI * NW == BM, "copy split");
     static_assert(MI >= 1 && NI >= 1, "wave tile");
-    static_assert((AJ + BJ) * (NS - 1) <= 48, "vmcnt budget");
+    static_assert((AJ + BJ) * NS <= 56, "vmcnt budget");
     static __device__ __forceinline__ int swz(int row) { return BK == 32 ? ((row >> 2) & 3) : ((row >> 1) & 7); }
 };
 
@@ -93,7 +104,8 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     const int layer = wg / tiles_per_layer;
     const int t0 = (wg - layer * tiles_per_layer) * BM;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
     const int wr = wave / WT, wt = wave % WT;
     const int l32 = lane & 31, g = lane >> 5;
     const uint16_t* xl = x + (long long)layer * xs_;
@@ -103,22 +115,22 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     // global -> LDS copy assignment: per tile, wave w moves rows
     // (w*AJ + j)*RPI .. +RPI of the W1 tile (j < AJ) and likewise of the token
     // tile; lane l supplies row l / CPR, slot l % CPR of its instruction.
-    const uint16_t* asrc[AJ];
-    const uint16_t* bsrc[BJ];
+    // Addresses are a wave-uniform base plus a 32-bit byte offset per lane.
+    uint32_t alane[AJ], blane[BJ];
 #pragma unroll
     for (int j = 0; j < AJ; ++j) {
         const int row = (wave * AJ + j) * RPI + lane / CPR;
         const int chunk = (lane % CPR) ^ C::swz(row);
-        asrc[j] = W1l + (long long)row * d + chunk * 8;
+        alane[j] = (uint32_t)(row * d + chunk * 8) * 2u;
     }
 #pragma unroll
     for (int j = 0; j < BJ; ++j) {
         const int row = (wave * BJ + j) * RPI + lane / CPR;
         const int chunk = (lane % CPR) ^ C::swz(row);
-        int tok = t0 + row;
-        tok = tok < T ? tok : T - 1;                       // rows past the end re-read the last token; never stored
-        bsrc[j] = xl + (long long)tok * d + chunk * 8;
+        const int last = T - 1 - t0;                       // rows past the end re-read the last token; never stored
+        blane[j] = (uint32_t)((row < last ? row : last) * d + chunk * 8) * 2u;
     }
+    const char* xtile = (const char*)(xl + (long long)t0 * d);
 
     f32x16 acc1[MI][NI];
     f32x16 acc2[EB32][NI];
@@ -135,125 +147,141 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc2[eb][ni][i] = 0.f;
 
-    const int NK = d / BK, NC = r / BN, NT = NK * NC;
+    const int NK = d / BK, NC = r / BN;
 
-    auto issue_tile = [&](int it) {
-        const int kt = it % NK, n = it / NK;
-        uint16_t* As = tiles + (it % NS) * STAGE_ELEMS;
+    // Requests the next tile in sequence into stage `slot`.  Past the end this
+    // re-reads the last tile into a stage nobody looks at again, which keeps the
+    // number of copies in flight constant, so one s_waitcnt immediate serves every
+    // iteration.  The tile coordinates advance by counters (no division).
+    int iss_kt = 0, iss_n = 0;
+    auto issue_tile = [&](int slot) {
+        uint16_t* As = tiles + slot * STAGE_ELEMS;
         uint16_t* Bs = As + BN * BK;
-        const long long aoff = (long long)n * BN * d + kt * BK;
-        const int boff = kt * BK;
+        const char* abase = (const char*)(W1l + ((long long)iss_n * BN * d + iss_kt * BK));
+        const char* bbase = xtile + (long long)iss_kt * BK * 2;
 #pragma unroll
         for (int j = 0; j < AJ; ++j)
-            __builtin_amdgcn_global_load_lds((gptr_t)(asrc[j] + aoff), (lptr_t)(As + (wave * AJ + j) * RPI * BK), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(abase + alane[j]), (lptr_t)(As + (wave * AJ + j) * RPI * BK), 16, 0, 0);
 #pragma unroll
         for (int j = 0; j < BJ; ++j)
-            __builtin_amdgcn_global_load_lds((gptr_t)(bsrc[j] + boff), (lptr_t)(Bs + (wave * BJ + j) * RPI * BK), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(bbase + blane[j]), (lptr_t)(Bs + (wave * BJ + j) * RPI * BK), 16, 0, 0);
+        if (iss_kt + 1 < NK) ++iss_kt;
+        else if (iss_n + 1 < NC) { iss_kt = 0; ++iss_n; }
     };
 
-    // LDS read offsets (elements) of this lane's A / B fragments per k-step
-    int aoffs[MI][BK / 16], boffs[NI][BK / 16];
+    // LDS read offsets (elements) of this lane's first A / B fragment at k-step 0.
+    // Block mi (ni) is a constant mi*32*BK further on (the swizzle only looks at
+    // row bits below 32), and k-step ks flips slot bits: offset ^ (ks * 16).
+    constexpr int KS = BK / 16;
+    const int arow0 = wr * WM + l32, brow0 = wt * WN + l32;
+    const int aoff0 = arow0 * BK + ((g ^ C::swz(arow0)) * 8);
+    const int boff0 = BN * BK + brow0 * BK + ((g ^ C::swz(brow0)) * 8);
+
+    bf16x8 fa[MI], fb[NI];
+    auto read_frags = [&](const uint16_t* st, auto ks_c) {
+        constexpr int ks = decltype(ks_c)::value;
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
+        for (int mi = 0; mi < MI; ++mi)
+            fa[mi] = __builtin_bit_cast(bf16x8, *(const u32x4*)(st + ((aoff0 ^ (ks * 16)) + mi * 32 * BK)));
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+            fb[ni] = __builtin_bit_cast(bf16x8, *(const u32x4*)(st + ((boff0 ^ (ks * 16)) + ni * 32 * BK)));
+    };
+    auto mfma_group = [&]() {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+                acc1[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc1[mi][ni], 0, 0, 0);
+    };
+    auto wg_barrier = [&]() {
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+
+    // Chunk n of h is complete in acc1: round it to bf16 and feed it to the
+    // second layer straight from the accumulator registers, then clear acc1.
+    // acc1[mi][ni][i] = h[token wt*WN + ni*32 + l32]
+    //                    [unit n*BN + wr*WM + mi*32 + 8*(i/4) + 4*g + i%4]
+    auto second_layer = [&](int n) {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
-            const int row = wr * WM + mi * 32 + l32;
-            aoffs[mi][ks] = row * BK + (((ks * 2 + g) ^ C::swz(row)) * 8);
-        }
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni) {
-            const int row = wt * WN + ni * 32 + l32;
-            boffs[ni][ks] = BN * BK + row * BK + (((ks * 2 + g) ^ C::swz(row)) * 8);
-        }
-    }
-
+            for (int s = 0; s < 2; ++s) {
+                const int unit0 = n * BN + wr * WM + mi * 32 + 16 * s + 4 * g;   // units unit0+0..3, unit0+8..11
+                float bias[8];
 #pragma unroll
-    for (int p = 0; p < NS - 1; ++p)
-        if (p < NT) issue_tile(p);
-
-    for (int it = 0; it < NT; ++it) {
-        const int kt = it % NK, n = it / NK;
-        // tile `it` has landed once at most the NS-2 younger tiles are in flight
-        if (it + NS - 2 < NT) __builtin_amdgcn_s_waitcnt(PAEP_VMCNT((AJ + BJ) * (NS - 2)));
-        else                  __builtin_amdgcn_s_waitcnt(PAEP_VMCNT(0));
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_barrier();                      // everyone's part of tile `it` is in LDS, and
-        asm volatile("" ::: "memory");                     // everyone is done reading stage (it-1) % NS
-        if (it + NS - 1 < NT) issue_tile(it + NS - 1);
-        {
-            const uint16_t* st = tiles + (it % NS) * STAGE_ELEMS;
+                for (int i = 0; i < 8; ++i) bias[i] = 0.f;
+                if (b1) {
 #pragma unroll
-            for (int ks = 0; ks < BK / 16; ++ks) {
-                bf16x8 a[MI], b[NI];
+                    for (int i = 0; i < 8; ++i)
+                        bias[i] = bf16_bits_to_f32(b1[(long long)layer * r + unit0 + (i & 3) + 8 * (i >> 2)]);
+                }
+                bf16x8 hb[NI];
 #pragma unroll
-                for (int mi = 0; mi < MI; ++mi)
-                    a[mi] = __builtin_bit_cast(bf16x8, *(const u32x4*)(st + aoffs[mi][ks]));
+                for (int ni = 0; ni < NI; ++ni) {
+                    float v[8];
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
-                    b[ni] = __builtin_bit_cast(bf16x8, *(const u32x4*)(st + boffs[ni][ks]));
+                    for (int i = 0; i < 8; ++i) {
+                        float h = round_to_bf16(acc1[mi][ni][8 * s + i] + bias[i]);
+                        if (act != 0) h = round_to_bf16(apply_act(h, act));
+                        v[i] = h;
+                    }
+                    u32x4 pk = u32x4{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]),
+                                     pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
+                    hb[ni] = __builtin_bit_cast(bf16x8, pk);
+                }
 #pragma unroll
-                for (int mi = 0; mi < MI; ++mi)
+                for (int eb = 0; eb < EB32; ++eb) {
+                    const int e = eb * 32 + l32;
+                    u32x4 wv = u32x4{0u, 0u, 0u, 0u};
+                    if (e < E) {
+                        const uint16_t* wp = W2l + (long long)e * r + unit0;
+                        const u32x2 lo = *(const u32x2*)wp;
+                        const u32x2 hi = *(const u32x2*)(wp + 8);
+                        wv = u32x4{lo[0], lo[1], hi[0], hi[1]};
+                    }
+                    const bf16x8 wa = __builtin_bit_cast(bf16x8, wv);
 #pragma unroll
                     for (int ni = 0; ni < NI; ++ni)
-                        acc1[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc1[mi][ni], 0, 0, 0);
-            }
-        }
-
-        if (kt == NK - 1) {
-            // chunk n of h is complete in acc1: feed it to the second layer.
-            // acc1[mi][ni][i] = h[token wt*WN + ni*32 + l32]
-            //                    [unit n*BN + wr*WM + mi*32 + 8*(i/4) + 4*g + i%4]
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi) {
-#pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    const int unit0 = n * BN + wr * WM + mi * 32 + 16 * s + 4 * g;   // units unit0+0..3, unit0+8..11
-                    float bias[8];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) bias[i] = 0.f;
-                    if (b1) {
-#pragma unroll
-                        for (int i = 0; i < 8; ++i)
-                            bias[i] = bf16_bits_to_f32(b1[(long long)layer * r + unit0 + (i & 3) + 8 * (i >> 2)]);
-                    }
-                    bf16x8 hb[NI];
-#pragma unroll
-                    for (int ni = 0; ni < NI; ++ni) {
-                        float v[8];
-#pragma unroll
-                        for (int i = 0; i < 8; ++i) {
-                            float h = round_to_bf16(acc1[mi][ni][8 * s + i] + bias[i]);
-                            if (act != 0) h = round_to_bf16(apply_act(h, act));
-                            v[i] = h;
-                        }
-                        u32x4 pk = u32x4{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]),
-                                         pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
-                        hb[ni] = __builtin_bit_cast(bf16x8, pk);
-                    }
-#pragma unroll
-                    for (int eb = 0; eb < EB32; ++eb) {
-                        const int e = eb * 32 + l32;
-                        u32x4 wv = u32x4{0u, 0u, 0u, 0u};
-                        if (e < E) {
-                            const uint16_t* wp = W2l + (long long)e * r + unit0;
-                            const u32x2 lo = *(const u32x2*)wp;
-                            const u32x2 hi = *(const u32x2*)(wp + 8);
-                            wv = u32x4{lo[0], lo[1], hi[0], hi[1]};
-                        }
-                        const bf16x8 wa = __builtin_bit_cast(bf16x8, wv);
-#pragma unroll
-                        for (int ni = 0; ni < NI; ++ni)
-                            acc2[eb][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, hb[ni], acc2[eb][ni], 0, 0, 0);
-                    }
+                        acc2[eb][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, hb[ni], acc2[eb][ni], 0, 0, 0);
                 }
+                __builtin_amdgcn_sched_barrier(0);          // keep the W2 fetches of later steps from piling up in registers
             }
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) acc1[mi][ni][i] = 0.f;
         }
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc1[mi][ni][i] = 0.f;
+    };
+
+    // NS tiles requested up front; tile 0 has landed for everyone after the barrier.
+#pragma unroll
+    for (int p = 0; p < NS; ++p) issue_tile(p);
+    __builtin_amdgcn_s_waitcnt(PAEP_VMCNT((AJ + BJ) * (NS - 1)));
+    wg_barrier();
+
+    constexpr int WAIT_NEXT = PAEP_VMCNT((AJ + BJ) * (NS - 2));   // next tile landed, NS-2 younger ones in flight
+    constexpr int WAIT_LDS = 0xC07F;                              // lgkmcnt(0) only
+
+    int slot = 0;                                                 // stage of the tile being multiplied
+    for (int n = 0; n < NC; ++n) {
+        for (int kt = 0; kt < NK; ++kt) {
+            const uint16_t* st = tiles + slot * STAGE_ELEMS;
+            static_for<KS>([&](auto ks_c) {
+                read_frags(st, ks_c);
+                mfma_group();
+            });
+            // this wave is done reading the tile and its copies of the next one have landed
+            __builtin_amdgcn_s_waitcnt(WAIT_NEXT & WAIT_LDS);
+            wg_barrier();
+            issue_tile(slot);
+            slot = (slot + 1 == NS) ? 0 : slot + 1;
+        }
+        second_layer(n);
     }
     __syncthreads();                                       // all tile reads done before LDS is reused
 
@@ -316,7 +344,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
 // Mid: 256 tokens x 128 hidden units, 8 waves side by side along tokens, which
 // keeps the score accumulators at E/2 registers per lane (E up to 256).
 // Small: 128 x 128, 4 waves, any r that is a multiple of 128 and short inputs.
-typedef PfCfg<256, 256, 32, 4, 2, 4, 1> CfgBig;
+typedef PfCfg<256, 256, 64, 2, 2, 4, 1> CfgBig;
 typedef PfCfg<256, 128, 32, 4, 1, 8, 1> CfgMid;
 typedef PfCfg<128, 128, 32, 4, 2, 2, 2> CfgSmall;
 typedef PfCfg<128, 128, 32, 4, 1, 4, 1> CfgSmallWide;
