@@ -126,6 +126,9 @@ class Runner:
             roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
                     "kernel": "decode_partial_kernel+decode_finalize_kernel", "kernel_ms": round(predict_ms, 4)}
+        self.i = 0                       # one untimed step on bank 0, whose weights the labels were drawn for
+        self.step()
+        self.torch.cuda.synchronize()
         return {"T": T, "path": self.path, "ms_per_step": round(ms_step, 4),
                 "value": round(T * w.L / (ms_step * 1e-3), 1), "roofline": roof,
                 "score_layer0": self.counters[0].cpu().numpy().tolist(), "weight_banks": self.n_banks}

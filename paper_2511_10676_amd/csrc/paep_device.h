@@ -143,6 +143,50 @@ __device__ __forceinline__ void row_softmax_topk_any(const float* zrow, int E, i
     else              row_softmax_topk<32, G>(zrow, E, k, g, idx_row, probs_row);
 }
 
+// Softmax + top-k of one row held in registers by a whole wave: lane l owns
+// z[v] = score of expert l + 64*v (v < NV).  k rounds of "wave-wide maximum
+// of the keys still in play"; the lane that owns the winner retires it.  Lane
+// j keeps the j-th winner and writes output j.  All reductions are xor
+// butterflies, so the result does not depend on scheduling.
+template <int NV>
+__device__ __forceinline__ void wave_softmax_topk(const float (&z)[NV], int E, int k, int lane,
+                                                  int32_t* idx_row, float* probs_row)
+{
+    uint64_t key[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int e = lane + 64 * v;
+        key[v] = (e < E) ? make_key(z[v], e) : 0ull;
+    }
+    uint64_t mine = 0ull;
+    for (int j = 0; j < k; ++j) {
+        uint64_t best = key[0];
+#pragma unroll
+        for (int v = 1; v < NV; ++v) best = key[v] > best ? key[v] : best;
+#pragma unroll
+        for (int mask = 1; mask < 64; mask <<= 1) {
+            const uint64_t o = __shfl_xor((unsigned long long)best, mask, 64);
+            best = o > best ? o : best;
+        }
+#pragma unroll
+        for (int v = 0; v < NV; ++v) key[v] = (key[v] == best) ? 0ull : key[v];
+        if (lane == j) mine = best;
+    }
+    const float m = key_score(__shfl((unsigned long long)mine, 0, 64));     // row maximum
+    float s = 0.0f;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int e = lane + 64 * v;
+        if (e < E && z[v] == z[v]) s += __expf(z[v] - m);
+    }
+#pragma unroll
+    for (int mask = 1; mask < 64; mask <<= 1) s += __shfl_xor(s, mask, 64);
+    if (lane < k) {
+        idx_row[lane] = key_expert(mine);
+        probs_row[lane] = __expf(key_score(mine) - m) / s;
+    }
+}
+
 // Same, for kernels that only accept k <= 16 (keeps their register budget small).
 template <int G>
 __device__ __forceinline__ void row_softmax_topk_upto16(const float* zrow, int E, int k, int g,

@@ -3,122 +3,158 @@
 // At a handful of tokens the predictor is a weight-streaming problem: every
 // byte of W1 (r x d) and W2 (E x r) is needed once and the arithmetic per byte
 // is tiny, so the kernel is organised around reading the weights from HBM
-// exactly once, coalesced, with many loads in flight.  One predictor belongs
-// to one layer (paper section 4.2) and a layer is only ~8 MB, so all layers of
-// a call are spread over one grid.
+// exactly once, coalesced, with many loads in flight and nothing in the way.
+// One predictor belongs to one layer (paper section 4.2) and a layer is only
+// ~8 MB, so all layers of a call are spread over one grid.
 //
 // Kernel 1 (partial): the inner width r is cut into slices of RS = 64 hidden
 // units; workgroup (slice, layer) owns W1[slice rows, :] and W2[:, slice].
-// Wave w streams 16 rows of W1 straight from global memory into the A operand
-// of v_mfma_f32_16x16x32_bf16 (each lane reads 16 contiguous bytes of one
-// row), the tokens come from a small LDS tile as the B operand (tokens padded
-// to a multiple of 16: the matrix cores have throughput to spare here), so the
-// slice of the hidden vector h^T[64, T] lands in registers.  It is rounded to
-// bf16 (bias and activation applied), parked in LDS, and multiplied by the
-// W2 column slice with the same instruction, which gives this slice's
-// contribution to the scores; that goes to the workspace as fp32
-// partial[layer][slice][t][e].
+// Its four waves split d into quarters.  A wave streams its quarter of the 64
+// rows straight from global memory into the A operand of
+// v_mfma_f32_16x16x32_bf16 (a lane reads 16 contiguous bytes of one row) and
+// the matching 16 bytes of each token into the B operand (tokens padded to a
+// multiple of 16 by masking lanes; the token block is small and stays in
+// cache), two batches of loads in flight, no LDS and no barrier in the loop.
+// The four partial sums of h^T[64, T] are added through LDS in a fixed order,
+// rounded to bf16 (bias and activation applied), and multiplied by the W2
+// column slice with the same instruction; that is this slice's contribution to
+// the scores and goes to the workspace as fp32 partial[layer][slice][t][e].
 //
-// Kernel 2 (finalize): adds the slices in ascending order (fixed order, so
-// the result is reproducible), adds b2, and runs softmax + top-k per token
-// (eq. 1 and eq. 4) out of LDS.
+// Kernel 2 (finalize): one wave per token adds the slices in ascending order
+// (fixed order, so the result is reproducible; up to 32 loads in flight), adds b2, and runs softmax and
+// top-k (eq. 1 and eq. 4) in registers with wave shuffles.
+#include <type_traits>
+
 #include "paep_device.h"
 #include "paep_internal.h"
 
 namespace paep {
 
 static constexpr int DEC_THREADS = 256;
-static constexpr int RS = 64;            // hidden units per workgroup (4 waves x 16 rows)
-static constexpr int KC = 256;           // d-chunk staged in LDS per step
-static constexpr int KSTEPS = KC / 32;   // MFMA k-steps per chunk
-static constexpr int XPAD = 8;           // bf16 elements of row padding in LDS
+static constexpr int RS = 64;            // hidden units per workgroup
+static constexpr int RB = RS / 16;       // 16-row blocks per workgroup
 static constexpr int HPAD = 8;
 
-template <int TB>   // 16-token blocks: T <= 16 * TB
+template <int TB, int U>   // 16-token blocks (T <= 16 * TB); k-steps per load batch
 __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(
     int T, int d, int r, int E, int act, long long xs_, long long w1s, long long w2s,
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ W1, const uint16_t* __restrict__ W2,
     const uint16_t* __restrict__ b1, float* __restrict__ partial)
 {
     constexpr int TP = 16 * TB;
-    __shared__ __attribute__((aligned(16))) uint16_t xt[TP * (KC + XPAD)];
-    __shared__ __attribute__((aligned(16))) uint16_t ht[TP * (RS + HPAD)];
+    __shared__ __attribute__((aligned(16))) float hsum[4][RB * TB * 64 * 4];      // per-wave partial h
+    __shared__ __attribute__((aligned(16))) uint16_t ht[TP * (RS + HPAD)];        // h as bf16, [token][unit]
 
     const int slice = blockIdx.x, layer = blockIdx.y, S = gridDim.x;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int m = lane & 15, kg = lane >> 4;
     const uint16_t* xl = x + (long long)layer * xs_;
     const uint16_t* W1l = W1 + (long long)layer * w1s;
     const uint16_t* W2l = W2 + (long long)layer * w2s;
 
-    const int j0 = slice * RS + wave * 16;               // this wave's first hidden unit
-    const uint16_t* arow = W1l + (long long)(j0 + m) * d + kg * 8;
+    // this wave's quarter of d
+    const int kq = d / 4, k0 = wave * kq;
+    const int nsteps = kq / 32;                               // MFMA k-steps per wave
+    const uint16_t* arow = W1l + (long long)(slice * RS + m) * d + k0 + kg * 8;   // + rb*16*d + step*32
+    const uint16_t* brow = xl + (long long)m * d + k0 + kg * 8;                  // + tb*16*d + step*32
+    bool tok_ok[TB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) tok_ok[tb] = (tb * 16 + m) < T;
 
-    f32x4 acc[TB];
+    // W2 fragments of this wave's first two expert blocks, requested now and used at the very end
+    constexpr int NPF = 2;
+    const int EB = (E + 15) / 16;
+    u32x4 w2pf[NPF][RS / 32];
 #pragma unroll
-    for (int tb = 0; tb < TB; ++tb) acc[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    const int nchunks = d / KC;
-    u32x4 a_next[KSTEPS], a_cur[KSTEPS];
+    for (int j = 0; j < NPF; ++j) {
+        const int e_row = (wave + 4 * j) * 16 + m;
 #pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) a_next[s] = *(const u32x4*)(arow + s * 32);
-
-    for (int c = 0; c < nchunks; ++c) {
-#pragma unroll
-        for (int s = 0; s < KSTEPS; ++s) a_cur[s] = a_next[s];
-        if (c + 1 < nchunks) {
-#pragma unroll
-            for (int s = 0; s < KSTEPS; ++s) a_next[s] = *(const u32x4*)(arow + (c + 1) * KC + s * 32);
+        for (int s = 0; s < RS / 32; ++s) {
+            w2pf[j][s] = u32x4{0u, 0u, 0u, 0u};
+            if (e_row < E) w2pf[j][s] = *(const u32x4*)(W2l + (long long)e_row * r + slice * RS + s * 32 + kg * 8);
         }
-        __syncthreads();                                  // previous chunk's LDS reads are done
-        for (int i = tid; i < TP * (KC / 8); i += DEC_THREADS) {
-            const int t = i / (KC / 8), cv = i - t * (KC / 8);
-            u32x4 v = u32x4{0u, 0u, 0u, 0u};
-            if (t < T) v = *(const u32x4*)(xl + (long long)t * d + c * KC + cv * 8);
-            *(u32x4*)(xt + t * (KC + XPAD) + cv * 8) = v;
-        }
-        __syncthreads();
+    }
+
+    f32x4 acc[RB][TB];
 #pragma unroll
-        for (int s = 0; s < KSTEPS; ++s) {
-            const bf16x8 a = __builtin_bit_cast(bf16x8, a_cur[s]);
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) acc[rb][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    u32x4 fa[2][U][RB], fb[2][U][TB];
+    auto load_batch = [&](auto buf_c, int step0) {
+        constexpr int buf = decltype(buf_c)::value;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int off = (step0 + u) * 32;
+            const bool live = step0 + u < nsteps;             // wave-uniform; steps past the end multiply zeros
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                fa[buf][u][rb] = u32x4{0u, 0u, 0u, 0u};
+                if (live) fa[buf][u][rb] = *(const u32x4*)(arow + (long long)rb * 16 * d + off);
+            }
 #pragma unroll
             for (int tb = 0; tb < TB; ++tb) {
-                const u32x4 bv = *(const u32x4*)(xt + (tb * 16 + m) * (KC + XPAD) + s * 32 + kg * 8);
-                acc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bv), acc[tb], 0, 0, 0);
+                fb[buf][u][tb] = u32x4{0u, 0u, 0u, 0u};
+                if (live && tok_ok[tb]) fb[buf][u][tb] = *(const u32x4*)(brow + (long long)tb * 16 * d + off);
             }
         }
+    };
+    auto mma_batch = [&](auto buf_c) {
+        constexpr int buf = decltype(buf_c)::value;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int tb = 0; tb < TB; ++tb)
+                    acc[rb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8, fa[buf][u][rb]), __builtin_bit_cast(bf16x8, fb[buf][u][tb]),
+                        acc[rb][tb], 0, 0, 0);
+    };
+
+    // batches alternate between two register sets: one is being filled while the other is multiplied
+    load_batch(std::integral_constant<int, 0>{}, 0);
+    for (int s0 = 0; s0 < nsteps; s0 += 2 * U) {
+        load_batch(std::integral_constant<int, 1>{}, s0 + U);
+        mma_batch(std::integral_constant<int, 0>{});
+        load_batch(std::integral_constant<int, 0>{}, s0 + 2 * U);
+        mma_batch(std::integral_constant<int, 1>{});
     }
 
-    // acc[tb][i] = h[token tb*16 + m][hidden unit j0 + 4*kg + i]
-    float bias[4] = {0.f, 0.f, 0.f, 0.f};
-    if (b1) {
+    // acc[rb][tb][i] = partial h[token tb*16 + m][unit slice*RS + rb*16 + 4*kg + i] over this wave's quarter of d
 #pragma unroll
-        for (int i = 0; i < 4; ++i) bias[i] = bf16_bits_to_f32(b1[(long long)layer * r + j0 + 4 * kg + i]);
-    }
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-    for (int tb = 0; tb < TB; ++tb) {
-        float v[4];
+        for (int tb = 0; tb < TB; ++tb)
+            *(f32x4*)(&hsum[wave][((rb * TB + tb) * 64 + lane) * 4]) = acc[rb][tb];
+    __syncthreads();
+    for (int q = tid; q < RB * TB * 64; q += DEC_THREADS) {
+        const int ln = q & 63, blk = q >> 6, tb = blk % TB, rb = blk / TB;
+        const int unit = rb * 16 + 4 * (ln >> 4), tok = tb * 16 + (ln & 15);
+        f32x4 v = *(const f32x4*)(&hsum[0][q * 4]);
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+            const f32x4 o = *(const f32x4*)(&hsum[w][q * 4]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] += o[i];
+        }
+        float h[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            float h = round_to_bf16(acc[tb][i] + bias[i]);
-            if (act != 0) h = round_to_bf16(apply_act(h, act));
-            v[i] = h;
+            float t = v[i];
+            if (b1) t += bf16_bits_to_f32(b1[(long long)layer * r + slice * RS + unit + i]);
+            t = round_to_bf16(t);
+            if (act != 0) t = round_to_bf16(apply_act(t, act));
+            h[i] = t;
         }
-        u32x2 packed = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
-        *(u32x2*)(ht + (tb * 16 + m) * (RS + HPAD) + wave * 16 + 4 * kg) = packed;
+        *(u32x2*)(ht + tok * (RS + HPAD) + unit) = u32x2{pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3])};
     }
     __syncthreads();
 
     // scores of this slice: z^T[e, t] = W2[e, slice] . h^T[slice, t]
-    const int EB = (E + 15) / 16;
-    for (int eb = wave; eb < EB; eb += DEC_THREADS / 64) {
-        const int e_row = eb * 16 + m;
-        u32x4 wfrag[RS / 32];
-#pragma unroll
-        for (int s = 0; s < RS / 32; ++s) {
-            wfrag[s] = u32x4{0u, 0u, 0u, 0u};
-            if (e_row < E) wfrag[s] = *(const u32x4*)(W2l + (long long)e_row * r + slice * RS + s * 32 + kg * 8);
-        }
+    auto score_block = [&](int eb, const u32x4 (&wfrag)[RS / 32]) {
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb) {
             f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -132,49 +168,81 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(
             const int t = tb * 16 + m;
             if (t < T) {
                 float* dst = partial + (((long long)layer * S + slice) * T + t) * E + eb * 16 + 4 * kg;
+                if (eb * 16 + 4 * kg + 3 < E) {
+                    *(f32x4*)dst = z;
+                } else {
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (eb * 16 + 4 * kg + i < E) dst[i] = z[i];
+                    for (int i = 0; i < 4; ++i)
+                        if (eb * 16 + 4 * kg + i < E) dst[i] = z[i];
+                }
             }
         }
+    };
+#pragma unroll
+    for (int j = 0; j < NPF; ++j)
+        if (wave + 4 * j < EB) score_block(wave + 4 * j, w2pf[j]);
+    for (int eb = wave + 4 * NPF; eb < EB; eb += 4) {
+        const int e_row = eb * 16 + m;
+        u32x4 wfrag[RS / 32];
+#pragma unroll
+        for (int s = 0; s < RS / 32; ++s) {
+            wfrag[s] = u32x4{0u, 0u, 0u, 0u};
+            if (e_row < E) wfrag[s] = *(const u32x4*)(W2l + (long long)e_row * r + slice * RS + s * 32 + kg * 8);
+        }
+        score_block(eb, wfrag);
     }
 }
 
-static constexpr int FIN_G = 16;                          // lanes per token row
-static constexpr int FIN_ROWS = DEC_THREADS / FIN_G;      // rows per workgroup
+// One wave per token row: lane l owns experts l, l+64, ...  The slice partials
+// are summed in ascending slice order, eight loads in flight at a time.
+static constexpr int FIN_NV = 8;                          // experts per lane: E <= 512
 
 __global__ __launch_bounds__(DEC_THREADS) void decode_finalize_kernel(
     int T, int E, int k, int S, int rows_total, const float* __restrict__ partial,
     const uint16_t* __restrict__ b2, int32_t* __restrict__ idx, float* __restrict__ probs,
     float* __restrict__ logits)
 {
-    extern __shared__ float zs[];                         // [FIN_ROWS][E + 1]
-    const int tid = threadIdx.x;
-    const int row0 = blockIdx.x * FIN_ROWS;
-    const int ZP = E + 1;
-    for (int i = tid; i < FIN_ROWS * E; i += DEC_THREADS) {
-        const int rr = i / E, e = i - rr * E;
-        const int row = row0 + rr;
-        if (row < rows_total) {
-            const int layer = row / T, t = row - layer * T;
-            const float* src = partial + ((long long)layer * S * T + t) * E + e;
-            float z = 0.0f;
-            for (int s = 0; s < S; ++s) z += src[(long long)s * T * E];
-            if (b2) z += bf16_bits_to_f32(b2[(long long)layer * E + e]);
-            zs[rr * ZP + e] = z;
-            if (logits) logits[(long long)row * E + e] = z;
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * (DEC_THREADS / 64) + (threadIdx.x >> 6);
+    if (row >= rows_total) return;
+    const int layer = row / T, t = row - layer * T;
+    const long long sstride = (long long)T * E;
+    const float* src = partial + ((long long)layer * S * T + t) * E;
+    float z[FIN_NV];
+#pragma unroll
+    for (int v = 0; v < FIN_NV; ++v) {
+        const int e = lane + 64 * v;
+        float acc = 0.0f;
+        if (e < E) {
+            int s = 0;
+            for (; s + 32 <= S; s += 32) {
+                float p[32];
+#pragma unroll
+                for (int u = 0; u < 32; ++u) p[u] = src[(long long)(s + u) * sstride + e];
+#pragma unroll
+                for (int u = 0; u < 32; ++u) acc += p[u];
+            }
+            for (; s + 8 <= S; s += 8) {
+                float p[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) p[u] = src[(long long)(s + u) * sstride + e];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc += p[u];
+            }
+            for (; s < S; ++s) acc += src[(long long)s * sstride + e];
+            if (b2) acc += bf16_bits_to_f32(b2[(long long)layer * E + e]);
+            if (logits) logits[(long long)row * E + e] = acc;
         }
+        z[v] = acc;
     }
-    __syncthreads();
-    const int rr = tid / FIN_G, g = tid % FIN_G;
-    const int row = row0 + rr;
-    if (row < rows_total)
-        row_softmax_topk_any<FIN_G>(zs + rr * ZP, E, k, g, idx + (long long)row * k, probs + (long long)row * k);
+    wave_softmax_topk<FIN_NV>(z, E, k, lane, idx + (long long)row * k, probs + (long long)row * k);
 }
 
 bool decode_supported(const PredictArgs& a)
 {
-    return a.dtype == 1 && a.T >= 1 && a.T <= 64 && a.d % KC == 0 && a.r % RS == 0 && a.E <= 512 && a.k <= 32;
+    // each wave takes a quarter of d in k-steps of 32
+    return a.dtype == 1 && a.T >= 1 && a.T <= 64 && a.r % RS == 0 && a.d % 128 == 0 && a.E <= 64 * FIN_NV &&
+           a.k <= 32;
 }
 
 size_t decode_workspace_bytes(const PredictArgs& a)
@@ -188,22 +256,23 @@ hipError_t launch_predict_decode(const PredictArgs& a)
     dim3 grid(S, a.L);
     float* partial = (float*)a.workspace;
     const int TB = (a.T + 15) / 16;
-#define PAEP_LAUNCH_DEC(TBV)                                                                          \
-    hipLaunchKernelGGL(decode_partial_kernel<TBV>, grid, dim3(DEC_THREADS), 0, a.stream, a.T, a.d,    \
-                       a.r, a.E, a.act, a.x_stride, a.w1_stride, a.w2_stride, (const uint16_t*)a.x,   \
-                       (const uint16_t*)a.W1, (const uint16_t*)a.W2, (const uint16_t*)a.b1, partial)
+#define PAEP_LAUNCH_DEC(TBV, UV)                                                                      \
+    hipLaunchKernelGGL((decode_partial_kernel<TBV, UV>), grid, dim3(DEC_THREADS), 0, a.stream, a.T,   \
+                       a.d, a.r, a.E, a.act, a.x_stride, a.w1_stride, a.w2_stride,                    \
+                       (const uint16_t*)a.x, (const uint16_t*)a.W1, (const uint16_t*)a.W2,            \
+                       (const uint16_t*)a.b1, partial)
     switch (TB) {
-    case 1: PAEP_LAUNCH_DEC(1); break;
-    case 2: PAEP_LAUNCH_DEC(2); break;
-    case 3: PAEP_LAUNCH_DEC(3); break;
-    default: PAEP_LAUNCH_DEC(4); break;
+    case 1: PAEP_LAUNCH_DEC(1, 4); break;
+    case 2: PAEP_LAUNCH_DEC(2, 4); break;
+    case 3: PAEP_LAUNCH_DEC(3, 2); break;
+    default: PAEP_LAUNCH_DEC(4, 2); break;
     }
 #undef PAEP_LAUNCH_DEC
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     const int rows = a.L * a.T;
-    const size_t lds = sizeof(float) * (size_t)FIN_ROWS * (size_t)(a.E + 1);
-    hipLaunchKernelGGL(decode_finalize_kernel, dim3((rows + FIN_ROWS - 1) / FIN_ROWS), dim3(DEC_THREADS), lds,
+    const int rows_per_wg = DEC_THREADS / 64;
+    hipLaunchKernelGGL(decode_finalize_kernel, dim3((rows + rows_per_wg - 1) / rows_per_wg), dim3(DEC_THREADS), 0,
                        a.stream, a.T, a.E, a.k, S, rows, partial, (const uint16_t*)a.b2, a.idx, a.probs, a.logits);
     return hipGetLastError();
 }

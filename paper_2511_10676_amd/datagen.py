@@ -156,7 +156,10 @@ def plant_near_ties(w: Workload, layer: int, x: np.ndarray, W1: np.ndarray, W2: 
     ar = np.arange(n)
     gap = z[ar, a] - z[ar, b]
     delta = g.uniform(0.0, gap_hi, size=n)
-    xs = xs - ((gap - delta) / np.sum(v * v, axis=1))[:, None] * v
+    vv = np.sum(v * v, axis=1)
+    movable = vv > 0                     # duplicated W2 rows give v = 0: that row already ties exactly
+    step = np.where(movable, (gap - delta) / np.where(movable, vv, 1.0), 0.0)
+    xs = xs - step[:, None] * v
     xs = round_to_storage(xs.astype(np.float32), w.dtype).astype(np.float64)
     if w.dtype == "bf16":
         target = 0.5 * gap_hi
