@@ -89,7 +89,9 @@ size_t paep_predict_workspace_bytes(const paep_predict_desc* desc)
 {
     if (check_desc(desc) != PAEP_OK) return 0;
     const paep::PredictArgs a = to_args(desc);
-    if (resolve(desc, a) == PAEP_PATH_DECODE) return paep::decode_workspace_bytes(a);
+    const int path = resolve(desc, a);
+    if (path == PAEP_PATH_DECODE) return paep::decode_workspace_bytes(a);
+    if (path == PAEP_PATH_PREFILL) return paep::prefill_workspace_bytes(a);
     return 0;
 }
 
@@ -107,7 +109,8 @@ paep_status paep_predict(const paep_predict_desc* desc,
     paep::PredictArgs a = to_args(desc);
     const int path = resolve(desc, a);
     if (!path) return PAEP_ERR_UNSUPPORTED;
-    const size_t need = (path == PAEP_PATH_DECODE) ? paep::decode_workspace_bytes(a) : 0;
+    const size_t need = (path == PAEP_PATH_DECODE) ? paep::decode_workspace_bytes(a)
+                      : (path == PAEP_PATH_PREFILL) ? paep::prefill_workspace_bytes(a) : 0;
     if (need > 0 && (!workspace_dev || !aligned16(workspace_dev) || workspace_bytes < need)) return PAEP_ERR_WORKSPACE;
     if (desc->T == 0) return PAEP_OK;
 

@@ -35,6 +35,7 @@ hipError_t launch_predict_decode(const PredictArgs& a);
 
 // bf16 fused matrix-core kernel for large T
 bool prefill_supported(const PredictArgs& a);
+size_t prefill_workspace_bytes(const PredictArgs& a);
 hipError_t launch_predict_prefill(const PredictArgs& a);
 
 size_t group_workspace_bytes(int L, int T, int k, int E);

@@ -78,11 +78,12 @@ struct PfZRows {
 // EB32: 32-expert blocks (E <= 32 * EB32).
 template <class C, int EB32>
 __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
-    int T, int d, int r, int E, int k, int act, int tiles_per_layer, int total_wgs,
+    int T, int d, int r, int E, int k, int act, int tiles_per_layer, int total_wgs, int groups, int cpg,
     long long xs_, long long w1s, long long w2s,
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ W1, const uint16_t* __restrict__ W2,
     const uint16_t* __restrict__ b1, const uint16_t* __restrict__ b2,
-    int32_t* __restrict__ idx, float* __restrict__ probs, float* __restrict__ logits)
+    int32_t* __restrict__ idx, float* __restrict__ probs, float* __restrict__ logits,
+    float* __restrict__ zpart, int* __restrict__ tickets)
 {
     constexpr int BM = C::BM, BN = C::BN, BK = C::BK, NS = C::NS, WR = C::WR, WT = C::WT;
     constexpr int WM = C::WM, WN = C::WN, MI = C::MI, NI = C::NI, CPR = C::CPR, RPI = C::RPI;
@@ -92,17 +93,23 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     uint16_t* tiles = (uint16_t*)smem_raw;
     float* zs = (float*)smem_raw;                         // reused after the main loop
 
-    // Workgroups are dealt round-robin to the 8 XCDs; remap so that each XCD
-    // works through a contiguous range of (layer, token tile) and its L2
-    // sees one layer's W1 at a time.
+    // A work item is (layer, token tile, group of r-chunks).  Workgroups are
+    // dealt round-robin to the 8 XCDs; remap so that each XCD walks a contiguous
+    // range of items with the chunk group varying fastest.  The workgroups that
+    // run together on an XCD then cover a few token tiles times all chunk groups
+    // of one layer: every x tile is shared by `groups` workgroups and every W1
+    // chunk by several token tiles through that XCD's L2, instead of each
+    // workgroup pulling its own x tile from far memory once per chunk.
     int wg = blockIdx.x;
     {
         const int per = total_wgs / 8, rem = total_wgs % 8;
         const int xcd = wg % 8, slot = wg / 8;
         wg = xcd * per + (xcd < rem ? xcd : rem) + slot;
     }
-    const int layer = wg / tiles_per_layer;
-    const int t0 = (wg - layer * tiles_per_layer) * BM;
+    const int cg = wg % groups;
+    const int tile_id = wg / groups;                      // layer * tiles_per_layer + token tile
+    const int layer = tile_id / tiles_per_layer;
+    const int t0 = (tile_id - layer * tiles_per_layer) * BM;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
@@ -147,26 +154,38 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc2[eb][ni][i] = 0.f;
 
-    const int NK = d / BK, NC = r / BN;
+    const int NK = d / BK;
+    const int n_begin = cg * cpg, n_end = n_begin + cpg;     // this work item's chunks of r
 
-    // Requests the next tile in sequence into stage `slot`.  Past the end this
-    // re-reads the last tile into a stage nobody looks at again, which keeps the
-    // number of copies in flight constant, so one s_waitcnt immediate serves every
-    // iteration.  The tile coordinates advance by counters (no division).
-    int iss_kt = 0, iss_n = 0;
-    auto issue_tile = [&](int slot) {
+    // Global -> LDS requests for the next tile in sequence, one copy instruction
+    // ("piece") at a time so that they can be spread between the MFMAs instead
+    // of holding a wave in a burst of memory instructions.  Pieces 0..AJ-1 move
+    // this wave's rows of the W1 tile, AJ..AJ+BJ-1 its rows of the token tile.
+    // issue_advance() steps the tile coordinates (counters, no division); past
+    // the end it stays on the last tile, which is then re-read into a stage
+    // nobody looks at again: the number of copies in flight stays constant, so
+    // one s_waitcnt immediate serves every iteration.
+    constexpr int NP = AJ + BJ;
+    int iss_kt = 0, iss_n = n_begin;
+    auto issue_piece = [&](int slot, auto q_c) {
+        constexpr int q = decltype(q_c)::value;
         uint16_t* As = tiles + slot * STAGE_ELEMS;
-        uint16_t* Bs = As + BN * BK;
-        const char* abase = (const char*)(W1l + ((long long)iss_n * BN * d + iss_kt * BK));
-        const char* bbase = xtile + (long long)iss_kt * BK * 2;
-#pragma unroll
-        for (int j = 0; j < AJ; ++j)
-            __builtin_amdgcn_global_load_lds((gptr_t)(abase + alane[j]), (lptr_t)(As + (wave * AJ + j) * RPI * BK), 16, 0, 0);
-#pragma unroll
-        for (int j = 0; j < BJ; ++j)
-            __builtin_amdgcn_global_load_lds((gptr_t)(bbase + blane[j]), (lptr_t)(Bs + (wave * BJ + j) * RPI * BK), 16, 0, 0);
+        if constexpr (q < AJ) {
+            const char* abase = (const char*)(W1l + ((long long)iss_n * BN * d + iss_kt * BK));
+            __builtin_amdgcn_global_load_lds((gptr_t)(abase + alane[q]), (lptr_t)(As + (wave * AJ + q) * RPI * BK), 16, 0, 0);
+        } else {
+            const char* bbase = xtile + (long long)iss_kt * BK * 2;
+            __builtin_amdgcn_global_load_lds((gptr_t)(bbase + blane[q - AJ]),
+                                             (lptr_t)(As + BN * BK + (wave * BJ + (q - AJ)) * RPI * BK), 16, 0, 0);
+        }
+    };
+    auto issue_advance = [&]() {
         if (iss_kt + 1 < NK) ++iss_kt;
-        else if (iss_n + 1 < NC) { iss_kt = 0; ++iss_n; }
+        else if (iss_n + 1 < n_end) { iss_kt = 0; ++iss_n; }
+    };
+    auto issue_tile = [&](int slot) {
+        static_for<NP>([&](auto q_c) { issue_piece(slot, q_c); });
+        issue_advance();
     };
 
     // LDS read offsets (elements) of this lane's first A / B fragment at k-step 0.
@@ -177,22 +196,26 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     const int aoff0 = arow0 * BK + ((g ^ C::swz(arow0)) * 8);
     const int boff0 = BN * BK + brow0 * BK + ((g ^ C::swz(brow0)) * 8);
 
-    bf16x8 fa[MI], fb[NI];
-    auto read_frags = [&](const uint16_t* st, auto ks_c) {
-        constexpr int ks = decltype(ks_c)::value;
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-            fa[mi] = __builtin_bit_cast(bf16x8, *(const u32x4*)(st + ((aoff0 ^ (ks * 16)) + mi * 32 * BK)));
+    // Fragment registers.  B fragments are double-buffered by k-step parity; A
+    // fragments are single-buffered and refilled one by one as soon as the
+    // MFMAs that use them have been issued ("rolling"), so that LDS reads for
+    // the next k-step run under the current k-step's matrix work.
+    bf16x8 fa[MI], fb[2][NI];
+    auto read_a = [&](const uint16_t* st, auto ks_c, auto mi_c) {
+        constexpr int ks = decltype(ks_c)::value, mi = decltype(mi_c)::value;
+        fa[mi] = __builtin_bit_cast(bf16x8, *(const u32x4*)(st + ((aoff0 ^ (ks * 16)) + mi * 32 * BK)));
+    };
+    auto read_b = [&](const uint16_t* st, auto ks_c, auto buf_c) {
+        constexpr int ks = decltype(ks_c)::value, buf = decltype(buf_c)::value;
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
-            fb[ni] = __builtin_bit_cast(bf16x8, *(const u32x4*)(st + ((boff0 ^ (ks * 16)) + ni * 32 * BK)));
+            fb[buf][ni] = __builtin_bit_cast(bf16x8, *(const u32x4*)(st + ((boff0 ^ (ks * 16)) + ni * 32 * BK)));
     };
-    auto mfma_group = [&]() {
+    auto mfma_row = [&](auto mi_c, auto buf_c) {
+        constexpr int mi = decltype(mi_c)::value, buf = decltype(buf_c)::value;
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
-                acc1[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc1[mi][ni], 0, 0, 0);
+        for (int ni = 0; ni < NI; ++ni)
+            acc1[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[buf][ni], acc1[mi][ni], 0, 0, 0);
     };
     auto wg_barrier = [&]() {
         asm volatile("" ::: "memory");
@@ -259,27 +282,79 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     };
 
     // NS tiles requested up front; tile 0 has landed for everyone after the barrier.
+    // (The coordinates are advanced only NS-1 times: the main loop's first deferred
+    // half-copy repeats the second half of tile NS-1 and then advances.)
 #pragma unroll
-    for (int p = 0; p < NS; ++p) issue_tile(p);
+    for (int p = 0; p < NS; ++p) {
+        static_for<NP>([&](auto q_c) { issue_piece(p, q_c); });
+        if (p + 1 < NS || !((NS >= 3) && (NP % 2 == 0) && (NP / 2 <= MI))) issue_advance();
+    }
     __builtin_amdgcn_s_waitcnt(PAEP_VMCNT((AJ + BJ) * (NS - 1)));
     wg_barrier();
 
     constexpr int WAIT_NEXT = PAEP_VMCNT((AJ + BJ) * (NS - 2));   // next tile landed, NS-2 younger ones in flight
     constexpr int WAIT_LDS = 0xC07F;                              // lgkmcnt(0) only
 
+    // Main loop.  Per k-step: request the next step's B fragments, then for each
+    // 32-unit block issue its MFMAs and immediately refill its A fragment for the
+    // next step.  On a tile's last k-step the "next step" is the first of the next
+    // tile, so the workgroup barrier that hands over LDS stages sits at the top of
+    // that step: by then this wave has all its fragments of the current tile in
+    // registers and its copies of the next tile have landed.  The copies that
+    // refill the stage freed by that barrier are dealt out one per MFMA pair-row:
+    // the first half during this last k-step, the second half during the first
+    // k-step of the next tile (DEFER), or all at once when there are only two
+    // stages and the data is needed one tile later.
+    constexpr bool DEFER = (NS >= 3) && (NP % 2 == 0) && (NP / 2 <= MI);
+    constexpr int HALF = NP / 2;
     int slot = 0;                                                 // stage of the tile being multiplied
-    for (int n = 0; n < NC; ++n) {
+    int fill_slot = NS - 1;                                       // stage whose second half of copies is pending
+    {
+        static_for<MI>([&](auto mi_c) { read_a(tiles, IC<0>{}, mi_c); });
+        read_b(tiles, IC<0>{}, IC<0>{});
+    }
+    for (int n = n_begin; n < n_end; ++n) {
         for (int kt = 0; kt < NK; ++kt) {
             const uint16_t* st = tiles + slot * STAGE_ELEMS;
+            const int nslot = (slot + 1 == NS) ? 0 : slot + 1;
+            const uint16_t* stn = tiles + nslot * STAGE_ELEMS;
             static_for<KS>([&](auto ks_c) {
-                read_frags(st, ks_c);
-                mfma_group();
+                constexpr int ks = decltype(ks_c)::value;
+                constexpr int cur = ks & 1, nxt = cur ^ 1;
+                if constexpr (ks + 1 < KS) {
+                    read_b(st, IC<ks + 1>{}, IC<nxt>{});
+                    __builtin_amdgcn_sched_barrier(0);
+                    static_for<MI>([&](auto mi_c) {
+                        constexpr int mi = decltype(mi_c)::value;
+                        mfma_row(mi_c, IC<cur>{});
+                        __builtin_amdgcn_sched_barrier(0);
+                        if constexpr (DEFER && ks == 0 && mi < HALF) {
+                            // second half of the copies for the stage freed one tile ago
+                            // (on the very first tile this repeats copies the prologue made: harmless)
+                            issue_piece(fill_slot, IC<HALF + mi>{});
+                            if constexpr (mi == HALF - 1) issue_advance();
+                        }
+                        read_a(st, IC<ks + 1>{}, mi_c);
+                        __builtin_amdgcn_sched_barrier(0);
+                    });
+                } else {
+                    __builtin_amdgcn_s_waitcnt(WAIT_NEXT & WAIT_LDS);
+                    wg_barrier();
+                    if constexpr (!DEFER) issue_tile(slot);
+                    read_b(stn, IC<0>{}, IC<nxt>{});
+                    __builtin_amdgcn_sched_barrier(0);
+                    static_for<MI>([&](auto mi_c) {
+                        constexpr int mi = decltype(mi_c)::value;
+                        mfma_row(mi_c, IC<cur>{});
+                        __builtin_amdgcn_sched_barrier(0);
+                        if constexpr (DEFER && mi < HALF) issue_piece(slot, IC<mi>{});
+                        read_a(stn, IC<0>{}, mi_c);
+                        __builtin_amdgcn_sched_barrier(0);
+                    });
+                    fill_slot = slot;
+                }
             });
-            // this wave is done reading the tile and its copies of the next one have landed
-            __builtin_amdgcn_s_waitcnt(WAIT_NEXT & WAIT_LDS);
-            wg_barrier();
-            issue_tile(slot);
-            slot = (slot + 1 == NS) ? 0 : slot + 1;
+            slot = nslot;
         }
         second_layer(n);
     }
@@ -291,10 +366,12 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     // large); waves that share tokens add their parts there, wr = 0 first.
     constexpr int ZROWS = PfZRows<C, EB32>::value;
     constexpr int ZG = C::THREADS / ZROWS;                 // lanes per token row in the epilogue
-    static_assert(ZROWS % WN == 0 && (ZG == 2 || ZG == 4), "epilogue split");
+    static_assert(ZROWS % WN == 0 && (ZG == 1 || ZG == 2 || ZG == 4), "epilogue split");
     const int ZP = E + 1;
-#pragma unroll 1
-    for (int zp = 0; zp < BM / ZROWS; ++zp) {
+    const bool split = groups > 1;
+
+    // registers -> zs for token rows [zp*ZROWS, (zp+1)*ZROWS); b2 is added here only when r is not split
+    auto regs_to_lds = [&](int zp) {
         const bool mine = (wt * WN) / ZROWS == zp;
 #pragma unroll
         for (int pass = 0; pass < WR; ++pass) {
@@ -310,7 +387,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
                             if (e < E) {
                                 float v = acc2[eb][ni][i];
                                 if (pass == 0) {
-                                    if (b2) v += bf16_bits_to_f32(b2[(long long)layer * E + e]);
+                                    if (b2 && !split) v += bf16_bits_to_f32(b2[(long long)layer * E + e]);
                                 } else {
                                     v = zs[tl * ZP + e] + v;
                                 }
@@ -320,6 +397,9 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
             }
             __syncthreads();
         }
+    };
+    // zs -> idx, probs (and logits) for the same rows
+    auto finish_rows = [&](int zp) {
         const int tbase = t0 + zp * ZROWS;
         if (logits) {
             for (int i = tid; i < ZROWS * E; i += C::THREADS) {
@@ -327,16 +407,74 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
                 if (tbase + tl < T) logits[((long long)layer * T + tbase + tl) * E + e] = zs[tl * ZP + e];
             }
         }
-        {
-            const int tl = tid / ZG, gg = tid % ZG;
-            // the lanes of a group take the same branch (same token)
-            if (tbase + tl < T) {
-                const long long row = (long long)layer * T + tbase + tl;
-                row_softmax_topk_upto16<ZG>(zs + tl * ZP, E, k, gg, idx + row * k, probs + row * k);
-            }
+        const int tl = tid / ZG, gg = tid % ZG;
+        // the lanes of a group take the same branch (same token)
+        if (tbase + tl < T) {
+            const long long row = (long long)layer * T + tbase + tl;
+            row_softmax_topk_upto16<ZG>(zs + tl * ZP, E, k, gg, idx + row * k, probs + row * k);
+        }
+        __syncthreads();
+    };
+
+    if (!split) {
+#pragma unroll 1
+        for (int zp = 0; zp < BM / ZROWS; ++zp) {
+            regs_to_lds(zp);
+            finish_rows(zp);
+        }
+        return;
+    }
+
+    // r is split over `groups` workgroups: park this group's score tile in the
+    // workspace as zpart[tile][group][token][expert]; the workgroup that arrives
+    // last (ticket counter, release/acquire fences) adds the groups in ascending
+    // order -- a fixed order, whoever is last -- and finishes the rows.
+    float* zmine = zpart + ((long long)tile_id * groups + cg) * BM * E;
+#pragma unroll 1
+    for (int zp = 0; zp < BM / ZROWS; ++zp) {
+        regs_to_lds(zp);
+        for (int i = tid; i < ZROWS * E; i += C::THREADS) {
+            const int tl = i / E, e = i - tl * E;
+            zmine[(long long)(zp * ZROWS + tl) * E + e] = zs[tl * ZP + e];
         }
         __syncthreads();
     }
+    // One thread publishes for the workgroup: the barrier orders every thread's
+    // stores before its device-scope release fence, and its acquire fence before
+    // every thread's later loads (one L2 write-back / invalidate per workgroup,
+    // not one per thread).
+    __syncthreads();
+    int* flag = (int*)smem_raw;
+    if (tid == 0) {
+        __threadfence();
+        const int ticket = atomicAdd(&tickets[tile_id], 1);
+        if (ticket == groups - 1) __threadfence();
+        *flag = ticket;
+    }
+    __syncthreads();
+    const bool last = (*flag == groups - 1);
+    __syncthreads();
+    if (!last) return;
+    const float* zall = zpart + (long long)tile_id * groups * BM * E;
+#pragma unroll 1
+    for (int zp = 0; zp < BM / ZROWS; ++zp) {
+        for (int i = tid; i < ZROWS * E; i += C::THREADS) {
+            const int tl = i / E, e = i - tl * E;
+            const float* src = zall + (long long)(zp * ZROWS + tl) * E + e;
+            float v = 0.0f;
+            for (int q = 0; q < groups; ++q) v += src[(long long)q * BM * E];
+            if (b2) v += bf16_bits_to_f32(b2[(long long)layer * E + e]);
+            zs[tl * ZP + e] = v;
+        }
+        __syncthreads();
+        finish_rows(zp);
+    }
+}
+
+__global__ void prefill_clear_tickets(int* tickets, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) tickets[i] = 0;
 }
 
 // Configurations.  Big: 256 x 256 tiles, 8 waves, one workgroup per CU -- the
@@ -344,7 +482,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
 // Mid: 256 tokens x 128 hidden units, 8 waves side by side along tokens, which
 // keeps the score accumulators at E/2 registers per lane (E up to 256).
 // Small: 128 x 128, 4 waves, any r that is a multiple of 128 and short inputs.
-typedef PfCfg<256, 256, 64, 2, 2, 4, 1> CfgBig;
+typedef PfCfg<256, 256, 32, 4, 2, 4, 1> CfgBig;
 typedef PfCfg<256, 128, 32, 4, 1, 8, 1> CfgMid;
 typedef PfCfg<128, 128, 32, 4, 2, 2, 2> CfgSmall;
 typedef PfCfg<128, 128, 32, 4, 1, 4, 1> CfgSmallWide;
@@ -361,19 +499,55 @@ bool prefill_supported(const PredictArgs& a)
     return a.dtype == 1 && a.T >= 1 && a.d % 32 == 0 && a.r % 128 == 0 && a.E <= 256 && a.k <= 16;
 }
 
+// How many workgroups share one token tile (each takes r / BN / groups chunks
+// and the last one to finish adds their score tiles).  Splitting lets the
+// workgroups of one XCD share a token tile through L2 instead of each pulling
+// its own from far memory once per chunk (measured: 3.3x fewer bytes fetched
+// past L2 at 8 groups), but every extra group costs a pipeline fill, a score
+// tile written and re-read, and a device-scope fence.  Measured on the paper's
+// shapes it pays only when the token tile is large (d >= 4096: 2 MB per tile),
+// and then with two groups.
+template <class C>
+static int prefill_groups(const PredictArgs& a)
+{
+    const int NC = a.r / C::BN;
+    const long long tiles = (long long)((a.T + C::BM - 1) / C::BM) * a.L;
+    if (tiles < 64 || NC % 2 != 0) return 1;                // short inputs: one workgroup per tile, no workspace
+    return ((long long)a.d * C::BM * 2 >= (2ll << 20)) ? 2 : 1;
+}
+
+template <class C>
+static size_t cfg_workspace_bytes(const PredictArgs& a)
+{
+    const int groups = prefill_groups<C>(a);
+    if (groups == 1) return 0;
+    const size_t tiles = (size_t)((a.T + C::BM - 1) / C::BM) * a.L;
+    return tiles * groups * C::BM * a.E * sizeof(float) + ((tiles * sizeof(int) + 15) / 16) * 16;
+}
+
 template <class C, int EB32>
 static hipError_t launch_cfg(const PredictArgs& a)
 {
     const int tiles = (a.T + C::BM - 1) / C::BM;
-    const int total = tiles * a.L;
+    const int groups = prefill_groups<C>(a);
+    const int cpg = a.r / C::BN / groups;
+    const int total = tiles * a.L * groups;
     const size_t lds = cfg_lds_bytes<C, EB32>(a.E);
+    float* zpart = nullptr;
+    int* tickets = nullptr;
+    if (groups > 1) {
+        zpart = (float*)a.workspace;
+        tickets = (int*)((char*)a.workspace + (size_t)tiles * a.L * groups * C::BM * a.E * sizeof(float));
+        const int nt = tiles * a.L;
+        hipLaunchKernelGGL(prefill_clear_tickets, dim3((nt + 255) / 256), dim3(256), 0, a.stream, tickets, nt);
+    }
     auto kern = prefill_kernel<C, EB32>;
     hipError_t err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(kern, dim3(total), dim3(C::THREADS), lds, a.stream, a.T, a.d, a.r, a.E, a.k, a.act, tiles,
-                       total, a.x_stride, a.w1_stride, a.w2_stride, (const uint16_t*)a.x, (const uint16_t*)a.W1,
-                       (const uint16_t*)a.W2, (const uint16_t*)a.b1, (const uint16_t*)a.b2, a.idx, a.probs,
-                       a.logits);
+                       total, groups, cpg, a.x_stride, a.w1_stride, a.w2_stride, (const uint16_t*)a.x,
+                       (const uint16_t*)a.W1, (const uint16_t*)a.W2, (const uint16_t*)a.b1,
+                       (const uint16_t*)a.b2, a.idx, a.probs, a.logits, zpart, tickets);
     return hipGetLastError();
 }
 
@@ -381,14 +555,32 @@ static hipError_t launch_cfg(const PredictArgs& a)
 // that, more and smaller workgroups win.
 static bool enough_large_tiles(const PredictArgs& a) { return (long long)((a.T + 255) / 256) * a.L >= 128; }
 
-hipError_t launch_predict_prefill(const PredictArgs& a)
+// 0: small, 1: small wide, 2: big, 3: mid
+static int pick_cfg(const PredictArgs& a)
 {
     const bool large = enough_large_tiles(a);
-    const bool big_ok = large && (a.r % 256 == 0);
-    if (a.E <= 32)  return big_ok ? launch_cfg<CfgBig, 1>(a) : launch_cfg<CfgSmall, 1>(a);
-    if (a.E <= 64)  return big_ok ? launch_cfg<CfgBig, 2>(a) : launch_cfg<CfgSmall, 2>(a);
-    if (a.E <= 128) return large ? launch_cfg<CfgMid, 4>(a) : launch_cfg<CfgSmallWide, 4>(a);
-    return large ? launch_cfg<CfgMid, 8>(a) : launch_cfg<CfgSmallWide, 8>(a);
+    if (a.E <= 64) return (large && a.r % 256 == 0) ? 2 : 0;
+    return large ? 3 : 1;
+}
+
+size_t prefill_workspace_bytes(const PredictArgs& a)
+{
+    switch (pick_cfg(a)) {
+    case 2: return cfg_workspace_bytes<CfgBig>(a);
+    case 3: return cfg_workspace_bytes<CfgMid>(a);
+    case 1: return cfg_workspace_bytes<CfgSmallWide>(a);
+    default: return cfg_workspace_bytes<CfgSmall>(a);
+    }
+}
+
+hipError_t launch_predict_prefill(const PredictArgs& a)
+{
+    switch (pick_cfg(a)) {
+    case 2: return a.E <= 32 ? launch_cfg<CfgBig, 1>(a) : launch_cfg<CfgBig, 2>(a);
+    case 3: return a.E <= 128 ? launch_cfg<CfgMid, 4>(a) : launch_cfg<CfgMid, 8>(a);
+    case 1: return a.E <= 128 ? launch_cfg<CfgSmallWide, 4>(a) : launch_cfg<CfgSmallWide, 8>(a);
+    default: return a.E <= 32 ? launch_cfg<CfgSmall, 1>(a) : launch_cfg<CfgSmall, 2>(a);
+    }
 }
 
 }  // namespace paep

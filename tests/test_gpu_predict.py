@@ -148,13 +148,20 @@ def test_empty_call():
     assert o.idx.shape == (2, 0, 6)
 
 
-@pytest.mark.parametrize("E,k,r", [(64, 6, 256), (128, 8, 128), (256, 8, 384), (24, 2, 512)])
-def test_prefill_large_tile_configs_with_ragged_tail(E, k, r):
+@pytest.mark.parametrize("E,k,r,d,L,T", [
+    (64, 6, 256, 64, 4, 8229), (128, 8, 128, 64, 4, 8229), (256, 8, 384, 64, 4, 8229), (24, 2, 512, 64, 4, 8229),
+    # d = 4096: the token tile is large enough that r is split over two workgroups per tile
+    # (score tiles through the workspace, ticketed last-arriver reduction)
+    (64, 6, 512, 4096, 4, 8300), (200, 8, 256, 4096, 4, 8300),
+])
+def test_prefill_large_tile_configs_with_ragged_tail(E, k, r, d, L, T):
     """Enough tokens that the large-tile kernels are chosen, a token count that
     is not a multiple of any tile, every row checked."""
-    x, W1, W2, b1, b2 = _rand_layers(70 + E, L=4, T=8229, d=64, r=r, E=E, dtype="bf16", bias=True)
-    out, *_ = _run_and_check(x, W1, W2, b1, b2, k, "bf16", path="prefill", what=f"prefill large tiles E={E} r={r}")
+    x, W1, W2, b1, b2 = _rand_layers(70 + E, L=L, T=T, d=d, r=r, E=E, dtype="bf16", bias=True)
+    out, *_ = _run_and_check(x, W1, W2, b1, b2, k, "bf16", path="prefill", what=f"prefill large tiles E={E} r={r} d={d}")
     assert out.path == "prefill"
+    desc = B.make_desc(T, d, r, E, k, L, B.BF16)
+    assert (B.predict_workspace_bytes(desc) > 0) == (d >= 4096)
 
 
 # ------------------------------------------------------------------ paper-shaped, full size, sampled rows
