@@ -28,7 +28,6 @@ namespace paep {
 // s_waitcnt immediate that waits for vmcnt <= n and nothing else (gfx9 encoding)
 #define PAEP_VMCNT(n) ((((n) & 0xF) | (((n) >> 4) << 14)) | 0x0F70)
 
-typedef const void __attribute__((address_space(1)))* gptr_t;
 typedef void __attribute__((address_space(3)))* lptr_t;
 
 template <int V> using IC = std::integral_constant<int, V>;
@@ -134,8 +133,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     for (int j = 0; j < BJ; ++j) {
         const int row = (wave * BJ + j) * RPI + lane / CPR;
         const int chunk = (lane % CPR) ^ C::swz(row);
-        const int last = T - 1 - t0;                       // rows past the end re-read the last token; never stored
-        blane[j] = (uint32_t)((row < last ? row : last) * d + chunk * 8) * 2u;
+        blane[j] = (uint32_t)(row * d + chunk * 8) * 2u;   // rows past the end of the layer read as zero
     }
     const char* xtile = (const char*)(xl + (long long)t0 * d);
 
@@ -167,16 +165,26 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     // one s_waitcnt immediate serves every iteration.
     constexpr int NP = AJ + BJ;
     int iss_kt = 0, iss_n = n_begin;
+    // Buffer-addressed copies (buffer_load_dwordx4 ... lds): base and bounds in a
+    // scalar resource, a 32-bit lane offset, a scalar tile offset.  Token rows
+    // past the end of the layer fall outside the resource and read as zero.  (The
+    // flat-addressed form of this instruction makes the compiler wait for every
+    // outstanding LDS read before the next MFMA, which serialises the pipeline.)
+    const __amdgpu_buffer_rsrc_t rsrc_a =
+        __builtin_amdgcn_make_buffer_rsrc((void*)W1l, 0, (int)((long long)r * d * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_b =
+        __builtin_amdgcn_make_buffer_rsrc((void*)xtile, 0, (int)((long long)(T - t0) * d * 2), 0x00020000);
     auto issue_piece = [&](int slot, auto q_c) {
         constexpr int q = decltype(q_c)::value;
         uint16_t* As = tiles + slot * STAGE_ELEMS;
         if constexpr (q < AJ) {
-            const char* abase = (const char*)(W1l + ((long long)iss_n * BN * d + iss_kt * BK));
-            __builtin_amdgcn_global_load_lds((gptr_t)(abase + alane[q]), (lptr_t)(As + (wave * AJ + q) * RPI * BK), 16, 0, 0);
+            const int soff = (iss_n * BN * d + iss_kt * BK) * 2;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lptr_t)(As + (wave * AJ + q) * RPI * BK), 16,
+                                                     (int)alane[q], soff, 0, 0);
         } else {
-            const char* bbase = xtile + (long long)iss_kt * BK * 2;
-            __builtin_amdgcn_global_load_lds((gptr_t)(bbase + blane[q - AJ]),
-                                             (lptr_t)(As + BN * BK + (wave * BJ + (q - AJ)) * RPI * BK), 16, 0, 0);
+            const int soff = iss_kt * BK * 2;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lptr_t)(As + BN * BK + (wave * BJ + (q - AJ)) * RPI * BK),
+                                                     16, (int)blane[q - AJ], soff, 0, 0);
         }
     };
     auto issue_advance = [&]() {
@@ -281,19 +289,30 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
                 for (int i = 0; i < 16; ++i) acc1[mi][ni][i] = 0.f;
     };
 
-    // NS tiles requested up front; tile 0 has landed for everyone after the barrier.
-    // (The coordinates are advanced only NS-1 times: the main loop's first deferred
-    // half-copy repeats the second half of tile NS-1 and then advances.)
-#pragma unroll
-    for (int p = 0; p < NS; ++p) {
-        static_for<NP>([&](auto q_c) { issue_piece(p, q_c); });
-        if (p + 1 < NS || !((NS >= 3) && (NP % 2 == 0) && (NP / 2 <= MI))) issue_advance();
-    }
-    __builtin_amdgcn_s_waitcnt(PAEP_VMCNT((AJ + BJ) * (NS - 1)));
-    wg_barrier();
-
-    constexpr int WAIT_NEXT = PAEP_VMCNT((AJ + BJ) * (NS - 2));   // next tile landed, NS-2 younger ones in flight
+    // Stage recycling.  With four or more stages (LAG) the stage refilled after
+    // the barrier inside tile `it` is the one tile it-1 used: every wave has
+    // certainly finished reading it (its fragments fed MFMAs issued before this
+    // barrier), so no wait on outstanding LDS reads is needed at the barrier.
+    // With fewer stages the current tile's own stage is refilled, which requires
+    // this wave's last fragment reads to have completed first.
+    constexpr bool LAG = (NS >= 4);
+    constexpr bool DEFER = (NS >= 3) && (NP % 2 == 0) && (NP / 2 <= MI);
+    constexpr int HALF = NP / 2;
+    constexpr int PRO = LAG ? NS - 1 : NS;                        // tiles requested before the loop
     constexpr int WAIT_LDS = 0xC07F;                              // lgkmcnt(0) only
+    // next tile landed: the younger tiles that may still be in flight
+    constexpr int WAIT_NEXT = LAG ? PAEP_VMCNT(NP * (NS - 3)) : (PAEP_VMCNT(NP * (NS - 2)) & WAIT_LDS);
+
+    // PRO tiles requested up front; tile 0 has landed for everyone after the barrier.
+    // (With DEFER the coordinates stay on the last requested tile: the main loop's
+    // first deferred half-copy repeats that tile's second half, then advances.)
+#pragma unroll
+    for (int p = 0; p < PRO; ++p) {
+        static_for<NP>([&](auto q_c) { issue_piece(p, q_c); });
+        if (p + 1 < PRO || !DEFER) issue_advance();
+    }
+    __builtin_amdgcn_s_waitcnt(PAEP_VMCNT(NP * (PRO - 1)));
+    wg_barrier();
 
     // Main loop.  Per k-step: request the next step's B fragments, then for each
     // 32-unit block issue its MFMAs and immediately refill its A fragment for the
@@ -305,13 +324,13 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     // the first half during this last k-step, the second half during the first
     // k-step of the next tile (DEFER), or all at once when there are only two
     // stages and the data is needed one tile later.
-    constexpr bool DEFER = (NS >= 3) && (NP % 2 == 0) && (NP / 2 <= MI);
-    constexpr int HALF = NP / 2;
     int slot = 0;                                                 // stage of the tile being multiplied
-    int fill_slot = NS - 1;                                       // stage whose second half of copies is pending
+    int free_slot = LAG ? NS - 1 : 0;                             // stage that the next barrier releases for refilling
+    int fill_slot = PRO - 1;                                      // stage whose second half of copies is pending
     {
         static_for<MI>([&](auto mi_c) { read_a(tiles, IC<0>{}, mi_c); });
         read_b(tiles, IC<0>{}, IC<0>{});
+        __builtin_amdgcn_s_waitcnt(WAIT_LDS);                     // nothing pending on loop entry
     }
     for (int n = n_begin; n < n_end; ++n) {
         for (int kt = 0; kt < NK; ++kt) {
@@ -329,7 +348,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
                         mfma_row(mi_c, IC<cur>{});
                         __builtin_amdgcn_sched_barrier(0);
                         if constexpr (DEFER && ks == 0 && mi < HALF) {
-                            // second half of the copies for the stage freed one tile ago
+                            // second half of the copies for the stage released one tile ago
                             // (on the very first tile this repeats copies the prologue made: harmless)
                             issue_piece(fill_slot, IC<HALF + mi>{});
                             if constexpr (mi == HALF - 1) issue_advance();
@@ -338,25 +357,27 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
                         __builtin_amdgcn_sched_barrier(0);
                     });
                 } else {
-                    __builtin_amdgcn_s_waitcnt(WAIT_NEXT & WAIT_LDS);
+                    __builtin_amdgcn_s_waitcnt(WAIT_NEXT);
                     wg_barrier();
-                    if constexpr (!DEFER) issue_tile(slot);
+                    if constexpr (!DEFER) issue_tile(free_slot);
                     read_b(stn, IC<0>{}, IC<nxt>{});
                     __builtin_amdgcn_sched_barrier(0);
                     static_for<MI>([&](auto mi_c) {
                         constexpr int mi = decltype(mi_c)::value;
                         mfma_row(mi_c, IC<cur>{});
                         __builtin_amdgcn_sched_barrier(0);
-                        if constexpr (DEFER && mi < HALF) issue_piece(slot, IC<mi>{});
+                        if constexpr (DEFER && mi < HALF) issue_piece(free_slot, IC<mi>{});
                         read_a(stn, IC<0>{}, mi_c);
                         __builtin_amdgcn_sched_barrier(0);
                     });
-                    fill_slot = slot;
+                    fill_slot = free_slot;
                 }
             });
+            free_slot = LAG ? slot : nslot;
             slot = nslot;
         }
         second_layer(n);
+        __builtin_amdgcn_s_waitcnt(WAIT_LDS);                     // next tile's first fragments have landed
     }
     __syncthreads();                                       // all tile reads done before LDS is reused
 
@@ -496,7 +517,9 @@ static size_t cfg_lds_bytes(int E)
 
 bool prefill_supported(const PredictArgs& a)
 {
-    return a.dtype == 1 && a.T >= 1 && a.d % 32 == 0 && a.r % 128 == 0 && a.E <= 256 && a.k <= 16;
+    // the copy offsets are 32-bit byte offsets into one layer's W1 and x
+    return a.dtype == 1 && a.T >= 1 && a.d % 32 == 0 && a.r % 128 == 0 && a.E <= 256 && a.k <= 16 &&
+           (long long)a.r * a.d * 2 < (1ll << 31) && ((long long)a.T + 256) * a.d * 2 < (1ll << 31);
 }
 
 // How many workgroups share one token tile (each takes r / BN / groups chunks
