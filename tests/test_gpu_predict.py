@@ -153,6 +153,8 @@ def test_empty_call():
     # d = 4096: the token tile is large enough that r is split over two workgroups per tile
     # (score tiles through the workspace, ticketed last-arriver reduction)
     (64, 6, 512, 4096, 4, 8300), (200, 8, 256, 4096, 4, 8300),
+    # several chunks of r per tile, many layers, a single layer with many tiles
+    (64, 6, 768, 64, 4, 8229), (64, 6, 1024, 64, 16, 8229), (128, 8, 640, 64, 9, 8229), (16, 2, 1280, 32, 1, 33000),
 ])
 def test_prefill_large_tile_configs_with_ragged_tail(E, k, r, d, L, T):
     """Enough tokens that the large-tile kernels are chosen, a token count that
