@@ -27,6 +27,30 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
 MALL_BYTES = 256 << 20
 
+# Bytes that crossed the L2 <-> fabric boundary per predict launch set, from two
+# rocprofv3 --pmc passes over this script (FETCH_SIZE, then WRITE_SIZE, KiB per
+# dispatch, summed over the predict kernels), each scaled by what the counter
+# reads for the 1 GiB device copy of --copy-probe-mib in the same run (FETCH_SIZE
+# reads half the copied bytes: factor 2.0; WRITE_SIZE reads them exactly: 1.0).
+# Keyed by a hash of the kernel sources: once a kernel changes, the figure no
+# longer describes it and the report says null.
+TRAFFIC_BYTES = {
+    ("prefill", "d8e6baa0f8670bdf"): {("deepseek_v2_lite", 4096): 3.845e9},
+    ("decode", "cfe8e4a2be9a0891"): {("deepseek_v2_lite", 1): 2.373e8, ("deepseek_v2_lite", 64): 3.088e8},
+}
+
+
+def measured_traffic(path, workload, T):
+    import hashlib
+    m = hashlib.sha256()
+    for f in ("predict_%s.hip" % path, "paep_device.h"):
+        try:
+            with open(os.path.join(ROOT, "paper_2511_10676_amd", "csrc", f), "rb") as fh:
+                m.update(fh.read())
+        except OSError:
+            return None
+    return TRAFFIC_BYTES.get((path, m.hexdigest()[:16]), {}).get((workload, T))
+
 
 def algorithmic_work(w, T):
     """Per layer call: flops and bytes the method itself must do/move
@@ -119,12 +143,12 @@ class Runner:
         if self.path == "prefill":
             ach = flops * w.L / (predict_ms * 1e-3) / 1e12
             roof = {"bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                    "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": measured_traffic("prefill", w.name, T),
                     "kernel": "prefill_kernel", "kernel_ms": round(predict_ms, 4)}
         else:
             ach = nbytes * w.L / (predict_ms * 1e-3) / 1e9
             roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": measured_traffic("decode", w.name, T),
                     "kernel": "decode_partial_kernel+decode_finalize_kernel", "kernel_ms": round(predict_ms, 4)}
         self.i = 0                       # one untimed step on bank 0, whose weights the labels were drawn for
         self.step()
@@ -165,6 +189,9 @@ def main():
     ap.add_argument("--T", type=int, default=0, help="tokens per layer (default: the workload's prefill size)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--sweep", action="store_true", help="also time the workload's other token counts")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="first run one plain device copy of this many MiB (a kernel of known traffic, for "
+                         "scaling hardware byte counters collected over the same run)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this library runs on one GPU; --gpus must be 1 (the path shards by tokens or layers "
@@ -177,6 +204,14 @@ def main():
     if w.dtype != "bf16":
         sys.exit("bench.py: choose a bf16 workload")
     T = args.T or w.prefill_T[0]
+    if args.copy_probe_mib > 0:
+        src = torch.empty(args.copy_probe_mib << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
     run = Runner(w, T)
     main_rep = run.report(args.steps, args.warmup)
     line = {
