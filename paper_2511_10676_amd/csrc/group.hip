@@ -4,7 +4,11 @@
 // third stage) derives from the selection: which experts are needed and which
 // tokens need each of them.
 //
-// Three launches, all layers of a call batched on gridDim.y:
+// Up to FUSED_MAX_ITEMS selections per layer (and as long as the layer's list
+// fits in LDS beside the histograms), one launch does all of it: a
+// workgroup of 16 waves per layer runs the same three phases out of LDS
+// (group_fused_kernel).  Longer layers take three launches, all layers of a
+// call batched on gridDim.y:
 //   hist     every wave owns WAVE_ITEMS consecutive flat positions and counts
 //            them per expert in its own LDS histogram, then stores that
 //            histogram row to the workspace: hist[layer][wave_chunk][E + 1]
@@ -94,10 +98,15 @@ __global__ __launch_bounds__(GROUP_THREADS) void group_scan_kernel(
         const int e = tid * per + q;
         if (q < per && e < E) {
             int run = 0;
-            for (int wc = 0; wc < nwc; ++wc) {
-                const int c = h[(long long)wc * (E + 1) + e];
-                h[(long long)wc * (E + 1) + e] = run;       // chunk's base inside the group
-                run += c;
+            for (int wc0 = 0; wc0 < nwc; wc0 += 16) {       // 16 loads in flight, then their running sums
+                int c[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) c[u] = (wc0 + u < nwc) ? h[(long long)(wc0 + u) * (E + 1) + e] : 0;
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    if (wc0 + u < nwc) h[(long long)(wc0 + u) * (E + 1) + e] = run;   // chunk's base inside the group
+                    run += c[u];
+                }
             }
             cnt[q] = run;
             counts[(long long)layer * E + e] = run;
@@ -176,6 +185,129 @@ __global__ __launch_bounds__(GROUP_THREADS) void group_scatter_kernel(
     }
 }
 
+
+// ---------------------------------------------------------------------------
+// One workgroup per layer, all three phases in LDS.
+//   lh[w][e]  phase 1: number of wave w's positions that chose expert e
+//             phase 2: turned into the wave's first slot for that expert
+//             phase 3: the wave's cursor
+// Wave w owns the contiguous positions [w*span, (w+1)*span), span a multiple
+// of 64, so groups come out in ascending position as in the three-launch path.
+// ---------------------------------------------------------------------------
+static constexpr int FUSED_THREADS = 1024;
+static constexpr int FUSED_WAVES = FUSED_THREADS / 64;
+static constexpr int FUSED_REGS = 32;                             // positions per lane, kept in registers
+static constexpr int FUSED_MAX_ITEMS = FUSED_WAVES * 64 * FUSED_REGS;   // 32768
+static constexpr size_t FUSED_MAX_LDS = 160 * 1024 - 256;           // per workgroup on gfx950, less the static part
+
+__global__ __launch_bounds__(FUSED_THREADS) void group_fused_kernel(
+    const int32_t* __restrict__ idx, int n, int E, int nbits,
+    int32_t* __restrict__ counts, int32_t* __restrict__ offsets, int32_t* __restrict__ token_pos,
+    int32_t* __restrict__ active, int32_t* __restrict__ n_active, int32_t* __restrict__ n_invalid)
+{
+    extern __shared__ int32_t lh[];                         // [FUSED_WAVES][E + 1], then the layer's output list [n]
+    __shared__ int32_t wave_tot[FUSED_WAVES][2];
+    const int layer = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int EP = E + 1;
+    const int32_t* src = idx + (long long)layer * n;
+    int32_t* dst = token_pos + (long long)layer * n;
+    int32_t* list = lh + FUSED_WAVES * EP;
+    for (int i = tid; i < FUSED_WAVES * EP; i += FUSED_THREADS) lh[i] = 0;
+    __syncthreads();
+
+    // the wave's positions are fetched once, all loads in flight together, and
+    // stay in registers for both passes: ev[j] = id at position first + 64*j + lane
+    const int span = ((n + FUSED_WAVES * 64 - 1) / (FUSED_WAVES * 64)) * 64;     // <= 64 * FUSED_REGS
+    const int first = wave * span;
+    int32_t* mine = lh + wave * EP;
+    int32_t ev[FUSED_REGS];
+#pragma unroll
+    for (int j = 0; j < FUSED_REGS; ++j) {
+        const int p = first + 64 * j + lane;
+        ev[j] = (64 * j < span && p < n) ? src[p] : -1;
+    }
+#pragma unroll
+    for (int j = 0; j < FUSED_REGS; ++j) {
+        const int p = first + 64 * j + lane;
+        if (64 * j < span && p < n) atomicAdd(&mine[(ev[j] >= 0 && ev[j] < E) ? ev[j] : E], 1);
+    }
+    __syncthreads();
+
+    // per expert: running sum over the waves -> bases, total -> count.  Thread
+    // t owns expert t, so a scan over threads is a scan over experts.
+    static_assert(MAX_E <= FUSED_THREADS, "one expert per thread");
+    int cnt = 0;
+    const int e_own = tid;
+    if (e_own < E) {
+        int run = 0;
+        for (int w = 0; w < FUSED_WAVES; ++w) {
+            const int c = lh[w * EP + e_own];
+            lh[w * EP + e_own] = run;
+            run += c;
+        }
+        cnt = run;
+        counts[(long long)layer * E + e_own] = run;
+    }
+    // block-wide exclusive scans of cnt and (cnt > 0): wave scan with shuffles, wave totals through LDS
+    int incl = cnt, incl_a = (cnt > 0);
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int a = __shfl_up(incl, off, 64), b = __shfl_up(incl_a, off, 64);
+        if (lane >= off) { incl += a; incl_a += b; }
+    }
+    if (lane == 63) { wave_tot[wave][0] = incl; wave_tot[wave][1] = incl_a; }
+    __syncthreads();
+    int woff = 0, woff_a = 0, total = 0, total_a = 0;
+    for (int w = 0; w < FUSED_WAVES; ++w) {
+        const int a = wave_tot[w][0], b = wave_tot[w][1];
+        if (w < wave) { woff += a; woff_a += b; }
+        total += a; total_a += b;
+    }
+    const int off_e = woff + incl - cnt, aoff = woff_a + incl_a - (cnt > 0);
+    int32_t* offs = offsets + (long long)layer * EP;
+    int32_t* act = active + (long long)layer * E;
+    if (e_own < E) {
+        offs[e_own] = off_e;
+        if (cnt > 0) act[aoff] = e_own;
+        for (int w = 0; w < FUSED_WAVES; ++w) lh[w * EP + e_own] += off_e;    // first slot of wave w for this expert
+    }
+    for (int i = total_a + tid; i < E; i += FUSED_THREADS) act[i] = -1;
+    if (tid == 0) {
+        offs[E] = total;
+        n_active[layer] = total_a;
+        int bad = 0;
+        for (int w = 0; w < FUSED_WAVES; ++w) bad += lh[w * EP + E];
+        n_invalid[layer] = bad;
+    }
+    __syncthreads();
+
+    // scatter: lanes holding the same expert find each other with ballots over
+    // the id bits; the highest such lane takes the group's slots from the
+    // wave's cursor with one LDS atomic and hands the old value to the others.
+    // The list is assembled in LDS (scattered 4-byte stores to global memory go
+    // through the memory pipeline one address at a time) and written out in order.
+#pragma unroll
+    for (int j = 0; j < FUSED_REGS; ++j) {
+        if (64 * j >= span) break;                          // wave-uniform
+        const int p = first + 64 * j + lane;
+        const int32_t e = ev[j];
+        const bool valid = (p < n && e >= 0 && e < E);
+        uint64_t same = __ballot(valid);
+        for (int b = 0; b < nbits; ++b) {
+            const bool bit = (e >> b) & 1;
+            const uint64_t set = __ballot(valid && bit);
+            same &= bit ? set : ~set;
+        }
+        const int leader = valid ? 63 - __clzll((long long)same) : lane;
+        int old = 0;
+        if (valid && lane == leader) old = atomicAdd(&mine[e], __popcll(same));
+        old = __shfl(old, leader, 64);
+        if (valid) list[old + __popcll(same & ((1ull << lane) - 1ull))] = p;
+    }
+    __syncthreads();
+    for (int i = tid; i < n; i += FUSED_THREADS) dst[i] = (i < total) ? list[i] : -1;   // -1 fills the unused tail
+}
+
 size_t group_workspace_bytes(int L, int T, int k, int E)
 {
     const long long n = (long long)T * k;
@@ -193,6 +325,17 @@ hipError_t launch_group(const int32_t* idx, int L, int T, int k, int E,
     const int nbc = block_chunks(n);
     int nbits = 0;
     while ((1 << nbits) < E) ++nbits;
+    const size_t lds = sizeof(int32_t) * ((size_t)FUSED_WAVES * (size_t)(E + 1) + (size_t)n);
+    if (n <= FUSED_MAX_ITEMS && lds <= FUSED_MAX_LDS) {
+        if (lds > 48 * 1024) {
+            hipError_t err = hipFuncSetAttribute((const void*)group_fused_kernel,
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (err != hipSuccess) return err;
+        }
+        hipLaunchKernelGGL(group_fused_kernel, dim3(L), dim3(FUSED_THREADS), lds, stream, idx, n, E, nbits, counts,
+                           offsets, token_pos, active, n_active, n_invalid);
+        return hipGetLastError();
+    }
     int32_t* hist = (int32_t*)workspace;
     if (nbc > 0)
         hipLaunchKernelGGL(group_hist_kernel, dim3(nbc, L), dim3(GROUP_THREADS), 0, stream, idx, n, E, nwc, hist);

@@ -40,6 +40,8 @@ def _check_group(idx, E):
     (1, 1, 1, 1), (0, 6, 64, 2), (1, 6, 64, 3), (9, 7, 64, 1), (64, 1, 16, 2), (65, 1, 16, 2),
     (171, 6, 64, 2), (1024, 1, 2, 1), (1025, 1, 300, 1), (4096, 6, 64, 3), (8192, 8, 128, 2),
     (8192, 2, 16, 2), (32768, 8, 256, 1), (700, 3, 1000, 2),
+    # either side of the single-launch limit of 32768 selections per layer
+    (4096, 8, 128, 2), (4097, 8, 128, 2), (32768, 1, 64, 1), (32769, 1, 64, 2), (2000, 16, 1024, 2), (65537, 1, 64, 2),
 ])
 def test_group_matches_oracle(T, k, E, L):
     g = np.random.default_rng(T * 31 + k * 7 + E)
@@ -69,6 +71,8 @@ def test_group_is_reproducible():
 @pytest.mark.parametrize("T,kp,kr,E,L", [
     (0, 6, 6, 64, 2), (1, 2, 2, 16, 1), (255, 6, 6, 64, 2), (257, 10, 6, 64, 3), (4096, 6, 6, 64, 2),
     (5000, 12, 8, 128, 2), (3000, 8, 8, 256, 1), (999, 3, 2, 16, 4), (500, 32, 5, 1000, 1),
+    # either side of the single-launch limit of 4096 tokens per layer; more than 8 ids per row
+    (4097, 6, 6, 64, 2), (20000, 8, 8, 256, 1), (6000, 20, 9, 700, 1), (300, 9, 32, 64, 2),
 ])
 def test_score_matches_oracle(T, kp, kr, E, L):
     g = np.random.default_rng(T + kp * 3 + E)
