@@ -456,7 +456,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
         regs_to_lds(zp);
         for (int i = tid; i < ZROWS * E; i += C::THREADS) {
             const int tl = i / E, e = i - tl * E;
-            zmine[(long long)(zp * ZROWS + tl) * E + e] = zs[tl * ZP + e];
+            if (t0 + zp * ZROWS + tl < T) zmine[(long long)(zp * ZROWS + tl) * E + e] = zs[tl * ZP + e];
         }
         __syncthreads();
     }
@@ -479,11 +479,19 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     const float* zall = zpart + (long long)tile_id * groups * BM * E;
 #pragma unroll 1
     for (int zp = 0; zp < BM / ZROWS; ++zp) {
+        if (t0 + zp * ZROWS >= T) break;                      // no tokens left in this tile (uniform)
         for (int i = tid; i < ZROWS * E; i += C::THREADS) {
             const int tl = i / E, e = i - tl * E;
+            if (t0 + zp * ZROWS + tl >= T) continue;
             const float* src = zall + (long long)(zp * ZROWS + tl) * E + e;
             float v = 0.0f;
-            for (int q = 0; q < groups; ++q) v += src[(long long)q * BM * E];
+            for (int q0 = 0; q0 < groups; q0 += 8) {          // eight loads in flight, added in ascending order
+                float part[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) part[u] = (q0 + u < groups) ? src[(long long)(q0 + u) * BM * E] : 0.0f;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v += part[u];
+            }
             if (b2) v += bf16_bits_to_f32(b2[(long long)layer * E + e]);
             zs[tl * ZP + e] = v;
         }
@@ -523,19 +531,28 @@ bool prefill_supported(const PredictArgs& a)
 }
 
 // How many workgroups share one token tile (each takes r / BN / groups chunks
-// and the last one to finish adds their score tiles).  Splitting lets the
-// workgroups of one XCD share a token tile through L2 instead of each pulling
-// its own from far memory once per chunk (measured: 3.3x fewer bytes fetched
-// past L2 at 8 groups), but every extra group costs a pipeline fill, a score
-// tile written and re-read, and a device-scope fence.  Measured on the paper's
-// shapes it pays only when the token tile is large (d >= 4096: 2 MB per tile),
-// and then with two groups.
+// and the last one to finish adds their score tiles).
+//  * Fewer tiles than CU slots (short inputs, down to a single tile per layer,
+//    where the kernel is a weight-streaming problem): split until there are
+//    about one and a half workgroups per CU, so that the whole chip pulls on
+//    HBM.
+//  * Many tiles: splitting lets the workgroups of one XCD share a token tile
+//    through L2 instead of each pulling its own from far memory once per chunk
+//    (measured: 3.3x fewer bytes fetched past L2 at 8 groups), but every extra
+//    group costs a pipeline fill, a score tile written and re-read, and a
+//    device-scope fence.  Measured on the paper's shapes it pays only when the
+//    token tile is large (d >= 4096: 2 MB per tile), and then with two groups.
 template <class C>
 static int prefill_groups(const PredictArgs& a)
 {
     const int NC = a.r / C::BN;
     const long long tiles = (long long)((a.T + C::BM - 1) / C::BM) * a.L;
-    if (tiles < 64 || NC % 2 != 0) return 1;                // short inputs: one workgroup per tile, no workspace
+    if (tiles < 256) {
+        int g = 1;
+        while (g < NC && (tiles * g < 384 || NC % g != 0)) ++g;
+        return g;
+    }
+    if (NC % 2 != 0) return 1;
     return ((long long)a.d * C::BM * 2 >= (2ll << 20)) ? 2 : 1;
 }
 

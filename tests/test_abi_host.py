@@ -91,13 +91,14 @@ def test_path_resolution_by_shape():
     assert B.resolve_path(_desc(T=4096, dtype=B.BF16, d=72, r=40, E=13, k=5)) == "simple"
     assert B.resolve_path(_desc(T=4096, dtype=B.BF16, d=2048, r=4096, E=256, k=8)) == "prefill"
     assert B.resolve_path(_desc(k=0)) == "invalid"
-    # prefill needs no workspace unless the token tile is large enough (d >= 4096) for r to be
-    # split over two co-scheduled workgroups: then two score tiles of 256 x E fp32 per tile plus a ticket
+    # with many tiles prefill needs no workspace unless the token tile is large enough (d >= 4096) for r to
+    # be split over two co-scheduled workgroups: then two score tiles of 256 x E fp32 per tile plus a ticket
     assert B.predict_workspace_bytes(_desc(T=4096, **ds)) == 0
     phi = dict(dtype=B.BF16, d=4096, r=1024, E=16, k=2, L=32)
     tiles = (8192 // 256) * 32
     assert B.predict_workspace_bytes(_desc(T=8192, **phi)) == tiles * 2 * 256 * 16 * 4 + tiles * 4
-    assert B.predict_workspace_bytes(_desc(T=100, **phi)) == 0          # few tiles: no split
+    # few tiles (32 of 128 tokens): r is split over all 8 chunks so that the whole chip streams the weights
+    assert B.predict_workspace_bytes(_desc(T=100, **phi)) == 32 * 8 * 128 * 16 * 4 + 32 * 4
     assert B.predict_workspace_bytes(_desc(k=0)) == 0
 
 
