@@ -512,7 +512,7 @@ __global__ void prefill_clear_tickets(int* tickets, int n)
 // keeps the score accumulators at E/2 registers per lane (E up to 256).
 // Small: 128 x 128, 4 waves, any r that is a multiple of 128 and short inputs.
 typedef PfCfg<256, 256, 32, 4, 2, 4, 1> CfgBig;
-typedef PfCfg<256, 128, 32, 4, 1, 8, 1> CfgMid;
+typedef PfCfg<256, 128, 64, 3, 1, 8, 1> CfgMid;
 typedef PfCfg<128, 128, 32, 4, 2, 2, 2> CfgSmall;
 typedef PfCfg<128, 128, 32, 4, 1, 4, 1> CfgSmallWide;
 
