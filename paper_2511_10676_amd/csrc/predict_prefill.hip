@@ -235,45 +235,67 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     // second layer straight from the accumulator registers, then clear acc1.
     // acc1[mi][ni][i] = h[token wt*WN + ni*32 + l32]
     //                    [unit n*BN + wr*WM + mi*32 + 8*(i/4) + 4*g + i%4]
+    // W2 fragments are requested first (with few enough experts that they fit in
+    // registers beside the conversion's temporaries), so that their latency runs
+    // under the rounding arithmetic; rows past E are clamped for the address and
+    // zeroed by a select, which keeps the loads free of branches.
+    constexpr bool EARLY_W2 = (EB32 <= 4);
+    auto w2_fragment = [&](int eb, int unit0) {
+        const int e = eb * 32 + l32;
+        const uint16_t* wp = W2l + (long long)(e < E ? e : E - 1) * r + unit0;
+        const u32x2 lo = *(const u32x2*)wp;
+        const u32x2 hi = *(const u32x2*)(wp + 8);
+        const bool ok = e < E;
+        return u32x4{ok ? lo[0] : 0u, ok ? lo[1] : 0u, ok ? hi[0] : 0u, ok ? hi[1] : 0u};
+    };
     auto second_layer = [&](int n) {
+        const bool plain = (act == 0) && (b1 == nullptr);     // uniform: no bias, identity activation
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 const int unit0 = n * BN + wr * WM + mi * 32 + 16 * s + 4 * g;   // units unit0+0..3, unit0+8..11
-                float bias[8];
+                u32x4 wv[EB32];
+                if constexpr (EARLY_W2) {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) bias[i] = 0.f;
-                if (b1) {
-#pragma unroll
-                    for (int i = 0; i < 8; ++i)
-                        bias[i] = bf16_bits_to_f32(b1[(long long)layer * r + unit0 + (i & 3) + 8 * (i >> 2)]);
+                    for (int eb = 0; eb < EB32; ++eb) wv[eb] = w2_fragment(eb, unit0);
                 }
                 bf16x8 hb[NI];
+                if (plain) {
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni) {
-                    float v[8];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        float h = round_to_bf16(acc1[mi][ni][8 * s + i] + bias[i]);
-                        if (act != 0) h = round_to_bf16(apply_act(h, act));
-                        v[i] = h;
+                    for (int ni = 0; ni < NI; ++ni) {
+                        const f32x16& a = acc1[mi][ni];
+                        u32x4 pk = u32x4{pack_bf16x2(a[8 * s + 0], a[8 * s + 1]), pack_bf16x2(a[8 * s + 2], a[8 * s + 3]),
+                                         pack_bf16x2(a[8 * s + 4], a[8 * s + 5]), pack_bf16x2(a[8 * s + 6], a[8 * s + 7])};
+                        hb[ni] = __builtin_bit_cast(bf16x8, pk);
                     }
-                    u32x4 pk = u32x4{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]),
-                                     pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
-                    hb[ni] = __builtin_bit_cast(bf16x8, pk);
+                } else {
+                    float bias[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) bias[i] = 0.f;
+                    if (b1) {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i)
+                            bias[i] = bf16_bits_to_f32(b1[(long long)layer * r + unit0 + (i & 3) + 8 * (i >> 2)]);
+                    }
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni) {
+                        float v[8];
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) {
+                            float h = acc1[mi][ni][8 * s + i] + bias[i];
+                            if (act != 0) h = apply_act(round_to_bf16(h), act);   // h is stored as bf16 before the activation
+                            v[i] = h;                                            // rounded to bf16 by the packing below
+                        }
+                        u32x4 pk = u32x4{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]),
+                                         pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
+                        hb[ni] = __builtin_bit_cast(bf16x8, pk);
+                    }
                 }
 #pragma unroll
                 for (int eb = 0; eb < EB32; ++eb) {
-                    const int e = eb * 32 + l32;
-                    u32x4 wv = u32x4{0u, 0u, 0u, 0u};
-                    if (e < E) {
-                        const uint16_t* wp = W2l + (long long)e * r + unit0;
-                        const u32x2 lo = *(const u32x2*)wp;
-                        const u32x2 hi = *(const u32x2*)(wp + 8);
-                        wv = u32x4{lo[0], lo[1], hi[0], hi[1]};
-                    }
-                    const bf16x8 wa = __builtin_bit_cast(bf16x8, wv);
+                    if constexpr (!EARLY_W2) wv[eb] = w2_fragment(eb, unit0);
+                    const bf16x8 wa = __builtin_bit_cast(bf16x8, wv[eb]);
 #pragma unroll
                     for (int ni = 0; ni < NI; ++ni)
                         acc2[eb][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, hb[ni], acc2[eb][ni], 0, 0, 0);
@@ -296,6 +318,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     // With fewer stages the current tile's own stage is refilled, which requires
     // this wave's last fragment reads to have completed first.
     constexpr bool LAG = (NS >= 4);
+    constexpr bool LATE_FRAGS = (EB32 >= 8);
     constexpr bool DEFER = (NS >= 3) && (NP % 2 == 0) && (NP / 2 <= MI);
     constexpr int HALF = NP / 2;
     constexpr int PRO = LAG ? NS - 1 : NS;                        // tiles requested before the loop
@@ -360,14 +383,17 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
                     __builtin_amdgcn_s_waitcnt(WAIT_NEXT);
                     wg_barrier();
                     if constexpr (!DEFER) issue_tile(free_slot);
-                    read_b(stn, IC<0>{}, IC<nxt>{});
+                    // With many experts the score accumulators leave no room to carry the next
+                    // tile's first fragments across the second layer: fetch them after it instead.
+                    const bool prefetch = !(LATE_FRAGS && kt == NK - 1);
+                    if (prefetch) read_b(stn, IC<0>{}, IC<nxt>{});
                     __builtin_amdgcn_sched_barrier(0);
                     static_for<MI>([&](auto mi_c) {
                         constexpr int mi = decltype(mi_c)::value;
                         mfma_row(mi_c, IC<cur>{});
                         __builtin_amdgcn_sched_barrier(0);
                         if constexpr (DEFER && mi < HALF) issue_piece(free_slot, IC<mi>{});
-                        read_a(stn, IC<0>{}, mi_c);
+                        if (prefetch) read_a(stn, IC<0>{}, mi_c);
                         __builtin_amdgcn_sched_barrier(0);
                     });
                     fill_slot = free_slot;
@@ -377,6 +403,11 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
             slot = nslot;
         }
         second_layer(n);
+        if constexpr (LATE_FRAGS) {
+            const uint16_t* stc = tiles + slot * STAGE_ELEMS;
+            static_for<MI>([&](auto mi_c) { read_a(stc, IC<0>{}, mi_c); });
+            read_b(stc, IC<0>{}, IC<(((KS - 1) & 1) ^ 1)>{});
+        }
         __builtin_amdgcn_s_waitcnt(WAIT_LDS);                     // next tile's first fragments have landed
     }
     __syncthreads();                                       // all tile reads done before LDS is reused
