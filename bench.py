@@ -158,6 +158,39 @@ class Runner:
                 "score_layer0": self.counters[0].cpu().numpy().tolist(), "weight_banks": self.n_banks}
 
 
+def device_ceilings(torch, B):
+    """What this device sustains for the two bounding resources, measured with the library's probes:
+    a coalesced streaming read of 1 GiB (fresh every launch: larger than the Infinity Cache) and of a
+    225 MB buffer (the size of one DeepSeek-shaped bank), and a register-only bf16 MFMA loop on every CU."""
+    out = {}
+    sink = torch.zeros(1 << 18, dtype=torch.uint8, device="cuda")
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    for name, nbytes, reps in (("read_1GiB_GBps", 1 << 30, 5), ("read_225MB_GBps", 225 << 20, 8)):
+        bufs = [torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(i + 1) for i in range(3)]
+        for b in bufs:
+            B.probe_read(b, sink)
+        torch.cuda.synchronize()
+        times = []
+        for i in range(reps * len(bufs)):
+            a, z = ev(), ev()
+            a.record(); B.probe_read(bufs[i % len(bufs)], sink); z.record()
+            torch.cuda.synchronize()
+            times.append(a.elapsed_time(z))
+        times.sort()
+        out[name] = round(nbytes / (times[len(times) // 2] * 1e-3) / 1e9, 1)
+        del bufs
+        torch.cuda.empty_cache()
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    B.probe_mfma(cus, 2000, sink)
+    torch.cuda.synchronize()
+    a, z = ev(), ev()
+    a.record(); flops = B.probe_mfma(cus, 40000, sink); z.record()
+    torch.cuda.synchronize()
+    out["mfma_bf16_loop_TFLOPs"] = round(flops / (a.elapsed_time(z) * 1e-3) / 1e12, 1)
+    out["note"] = "measured on this device by paep_probe_read / paep_probe_mfma (registers only, all CUs busy)"
+    return out
+
+
 def cpu_baseline(w, T, budget_s=20.0):
     """The CPU oracle, as it stands, on a bounded sample of the same workload."""
     import numpy as np
@@ -212,6 +245,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
+    from paper_2511_10676_amd import binding as B
+    ceilings = device_ceilings(torch, B)
     run = Runner(w, T)
     main_rep = run.report(args.steps, args.warmup)
     line = {
@@ -224,6 +259,7 @@ def main():
                                f"({main_rep['path']} path), step = predict + group_by_expert + score, all layers",
                    "weight_banks": main_rep["weight_banks"], "score_layer0": main_rep["score_layer0"]},
         "roofline": main_rep["roofline"],
+        "achievable": ceilings,
     }
     del run
     torch.cuda.empty_cache()

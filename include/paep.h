@@ -164,6 +164,24 @@ paep_status paep_score(const int32_t *idx_dev, int32_t k_pred,
                        int32_t L, int32_t T, int32_t E,
                        long long *counters_dev, void *stream);
 
+/*
+ * Device ceilings, measured: not part of the paper's method.  The benchmark
+ * runs them next to the predict kernels so that a roofline fraction can be
+ * read against what this device sustains as well as against the published peak.
+ *
+ * paep_probe_read: one launch that reads `bytes` (multiple of 16, 16-byte
+ *   aligned) from src_dev with coalesced 16-byte loads and folds them into
+ *   sink_dev (at least 65536 bytes; contents are meaningless).
+ * paep_probe_mfma: one launch of `workgroups` workgroups of eight waves, each
+ *   issuing 8 * iters v_mfma_f32_32x32x16_bf16 from registers; *flops_out
+ *   (host, may be NULL) receives the flops of the launch; sink_dev needs 4
+ *   bytes per workgroup.
+ * Both are asynchronous on `stream`; time them with events.
+ */
+paep_status paep_probe_read(const void *src_dev, size_t bytes, void *sink_dev, size_t sink_bytes, void *stream);
+paep_status paep_probe_mfma(int32_t workgroups, int32_t iters, void *sink_dev, size_t sink_bytes, void *stream,
+                            double *flops_out);
+
 const char *paep_status_string(paep_status s);
 
 /* Library version as major*10000 + minor*100 + patch. */

@@ -29,7 +29,7 @@ STATUS_NAMES = ["PAEP_OK", "PAEP_ERR_NULL", "PAEP_ERR_SHAPE", "PAEP_ERR_K", "PAE
 
 EXPORTS = ["paep_predict_workspace_bytes", "paep_predict_resolve_path", "paep_predict",
            "paep_group_workspace_bytes", "paep_group_by_expert", "paep_score",
-           "paep_status_string", "paep_version"]
+           "paep_probe_read", "paep_probe_mfma", "paep_status_string", "paep_version"]
 
 
 class PredictDesc(ctypes.Structure):
@@ -78,6 +78,10 @@ def lib() -> ctypes.CDLL:
         L.paep_group_by_expert.restype = ctypes.c_int
         L.paep_score.argtypes = [vp, i32, vp, i32, i32, i32, i32, vp, vp]
         L.paep_score.restype = ctypes.c_int
+        L.paep_probe_read.argtypes = [vp, sz, vp, sz, vp]
+        L.paep_probe_read.restype = ctypes.c_int
+        L.paep_probe_mfma.argtypes = [i32, i32, vp, sz, vp, ctypes.POINTER(ctypes.c_double)]
+        L.paep_probe_mfma.restype = ctypes.c_int
         L.paep_status_string.argtypes = [ctypes.c_int]
         L.paep_status_string.restype = ctypes.c_char_p
         L.paep_version.restype = ctypes.c_int
@@ -253,3 +257,23 @@ def score(idx: torch.Tensor, ref_idx: torch.Tensor, E: int, *, out: Optional[tor
     if st != 0:
         raise PaepError(st, "paep_score")
     return out
+
+
+def probe_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    """One launch of the streaming-read probe over all of `src` (device ceilings, not part of the method)."""
+    _need_device(src, sink)
+    st = lib().paep_probe_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink),
+                               sink.numel() * sink.element_size(), _stream_ptr(stream))
+    if st != 0:
+        raise PaepError(st, "paep_probe_read")
+
+
+def probe_mfma(workgroups: int, iters: int, sink: torch.Tensor, stream=None) -> float:
+    """One launch of the register-only matrix-instruction probe; returns the flops of the launch."""
+    _need_device(sink)
+    flops = ctypes.c_double(0.0)
+    st = lib().paep_probe_mfma(workgroups, iters, _ptr(sink), sink.numel() * sink.element_size(),
+                               _stream_ptr(stream), ctypes.byref(flops))
+    if st != 0:
+        raise PaepError(st, "paep_probe_mfma")
+    return flops.value

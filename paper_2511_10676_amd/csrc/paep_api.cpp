@@ -171,4 +171,25 @@ paep_status paep_score(const int32_t* idx_dev, int32_t k_pred, const int32_t* re
     return err == hipSuccess ? PAEP_OK : PAEP_ERR_HIP;
 }
 
+paep_status paep_probe_read(const void* src_dev, size_t bytes, void* sink_dev, size_t sink_bytes, void* stream)
+{
+    if (!src_dev || !sink_dev) return PAEP_ERR_NULL;
+    if (bytes % 16 != 0 || (reinterpret_cast<uintptr_t>(src_dev) & 15u)) return PAEP_ERR_ALIGN;
+    if (sink_bytes < 16u * paep::PROBE_READ_GROUPS) return PAEP_ERR_WORKSPACE;
+    const hipError_t err = paep::launch_probe_read(src_dev, bytes, sink_dev, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? PAEP_OK : PAEP_ERR_HIP;
+}
+
+paep_status paep_probe_mfma(int32_t workgroups, int32_t iters, void* sink_dev, size_t sink_bytes, void* stream,
+                            double* flops_out)
+{
+    if (workgroups < 1 || workgroups > 65536 || iters < 1) return PAEP_ERR_SHAPE;
+    if (!sink_dev) return PAEP_ERR_NULL;
+    if (sink_bytes < 4u * (size_t)workgroups) return PAEP_ERR_WORKSPACE;
+    // 8 waves per workgroup, 8 instructions per iteration, 2*32*32*16 flops each
+    if (flops_out) *flops_out = (double)workgroups * 8.0 * (double)iters * 8.0 * 32768.0;
+    const hipError_t err = paep::launch_probe_mfma(workgroups, iters, sink_dev, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? PAEP_OK : PAEP_ERR_HIP;
+}
+
 }  // extern "C"
