@@ -52,24 +52,25 @@ def measured_traffic(path, workload, T):
     return TRAFFIC_BYTES.get((path, m.hexdigest()[:16]), {}).get((workload, T))
 
 
-def algorithmic_work(w, T):
+def algorithmic_work(w, T, k=None):
     """Per layer call: flops and bytes the method itself must do/move
     (two weight matrices, x in, idx + probs out; h and the scores stay on chip)."""
     flops = 2.0 * w.r * (w.d + w.E) * T
     wbytes = 2.0 * w.r * (w.d + w.E)
-    nbytes = wbytes + 2.0 * T * w.d + 8.0 * T * w.k + (2.0 * w.E if w.zipf_bias else 0.0)
+    nbytes = wbytes + 2.0 * T * w.d + 8.0 * T * (k or w.k) + (2.0 * w.E if w.zipf_bias else 0.0)
     return flops, nbytes
 
 
 class Runner:
     """Device buffers for one workload at one token count, and the step."""
 
-    def __init__(self, w, T, n_banks=None, seed_layers=None):
+    def __init__(self, w, T, n_banks=None, k_pred=None):
         import numpy as np
         import torch
         from paper_2511_10676_amd import binding as B
         from paper_2511_10676_amd import datagen
         self.B, self.torch, self.w, self.T = B, torch, w, T
+        self.k_pred = kp = k_pred or w.k            # experts predicted per token (> w.k: over-provisioning, section 4.1)
         L = w.L
         bank_bytes = 2 * L * w.r * (w.d + w.E)
         if n_banks is None:
@@ -99,14 +100,14 @@ class Runner:
             self.W2.append(to_dev(np.stack([datagen.make_w2(w, l, bank) for l in range(L)])))
         self.setup_s = time.time() - t0
         dev = self.x.device
-        desc = B.make_desc(T, w.d, w.r, w.E, w.k, L, B.BF16)
+        desc = B.make_desc(T, w.d, w.r, w.E, kp, L, B.BF16)
         self.path = B.resolve_path(desc)
         ws = B.predict_workspace_bytes(desc)
         self.ws = torch.empty(max(ws, 16), dtype=torch.uint8, device=dev)
-        self.out = B.Prediction(torch.empty((L, T, w.k), dtype=torch.int32, device=dev),
-                                torch.empty((L, T, w.k), dtype=torch.float32, device=dev), None, self.path)
-        self.grp = B.alloc_grouping(L, T, w.k, w.E, dev)
-        self.gws = torch.empty(max(B.group_workspace_bytes(L, T, w.k, w.E), 16), dtype=torch.uint8, device=dev)
+        self.out = B.Prediction(torch.empty((L, T, kp), dtype=torch.int32, device=dev),
+                                torch.empty((L, T, kp), dtype=torch.float32, device=dev), None, self.path)
+        self.grp = B.alloc_grouping(L, T, kp, w.E, dev)
+        self.gws = torch.empty(max(B.group_workspace_bytes(L, T, kp, w.E), 16), dtype=torch.uint8, device=dev)
         self.counters = torch.empty((L, 4), dtype=torch.int64, device=dev)
         self.i = 0
 
@@ -116,30 +117,37 @@ class Runner:
         self.i += 1
         if ev is not None:
             ev[0].record()
-        B.predict(self.x, self.W1[bank], self.W2[bank], w.k, b2=self.b2, out=self.out, workspace=self.ws)
+        B.predict(self.x, self.W1[bank], self.W2[bank], self.k_pred, b2=self.b2, out=self.out, workspace=self.ws)
         if ev is not None:
             ev[1].record()
         B.group_by_expert(self.out.idx, w.E, out=self.grp, workspace=self.gws)
         B.score(self.out.idx, self.ref, w.E, out=self.counters)
+        if ev is not None:
+            ev[2].record()
 
     def timed(self, steps, warmup):
         torch = self.torch
         for _ in range(warmup):
             self.step()
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        evs = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for _ in range(steps)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for s in range(steps):
             self.step(evs[s])
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
-        predict_ms = sum(a.elapsed_time(b) for a, b in evs) / steps
-        return wall / steps * 1e3, predict_ms
+        predict = sorted(a.elapsed_time(b) for a, b, _ in evs)
+        whole = sorted(a.elapsed_time(c) for a, _, c in evs)
+        mean = lambda v: sum(v) / len(v)
+        std = lambda v: (sum((t - mean(v)) ** 2 for t in v) / len(v)) ** 0.5
+        self.stats = {"predict_ms_median": round(predict[len(predict) // 2], 4), "predict_ms_std": round(std(predict), 4),
+                      "step_gpu_ms_median": round(whole[len(whole) // 2], 4), "step_gpu_ms_std": round(std(whole), 4)}
+        return wall / steps * 1e3, mean(predict)
 
     def report(self, steps, warmup):
         w, T = self.w, self.T
         ms_step, predict_ms = self.timed(steps, warmup)
-        flops, nbytes = algorithmic_work(w, T)
+        flops, nbytes = algorithmic_work(w, T, self.k_pred)
         if self.path == "prefill":
             ach = flops * w.L / (predict_ms * 1e-3) / 1e12
             roof = {"bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -155,7 +163,8 @@ class Runner:
         self.torch.cuda.synchronize()
         return {"T": T, "path": self.path, "ms_per_step": round(ms_step, 4),
                 "value": round(T * w.L / (ms_step * 1e-3), 1), "roofline": roof,
-                "score_layer0": self.counters[0].cpu().numpy().tolist(), "weight_banks": self.n_banks}
+                "score_layer0": self.counters[0].cpu().numpy().tolist(), "weight_banks": self.n_banks,
+                "timing": self.stats}
 
 
 def device_ceilings(torch, B):
@@ -216,10 +225,13 @@ def cpu_baseline(w, T, budget_s=20.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="deepseek_v2_lite")
     ap.add_argument("--T", type=int, default=0, help="tokens per layer (default: the workload's prefill size)")
+    ap.add_argument("--k-pred", type=int, default=0,
+                    help="experts predicted per token (default: the workload's k; larger = over-provisioned "
+                         "prediction scored against the router's k labels)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--sweep", action="store_true", help="also time the workload's other token counts")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -247,7 +259,7 @@ def main():
         torch.cuda.empty_cache()
     from paper_2511_10676_amd import binding as B
     ceilings = device_ceilings(torch, B)
-    run = Runner(w, T)
+    run = Runner(w, T, k_pred=args.k_pred or None)
     main_rep = run.report(args.steps, args.warmup)
     line = {
         "metric": "predicted tokens*layers per second",
@@ -257,7 +269,10 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}-shaped: L={w.L} d={w.d} r={w.r} E={w.E} k={w.k}, T={T} tokens/layer "
                                f"({main_rep['path']} path), step = predict + group_by_expert + score, all layers",
-                   "weight_banks": main_rep["weight_banks"], "score_layer0": main_rep["score_layer0"]},
+                   "k_pred": run.k_pred, "weight_banks": main_rep["weight_banks"],
+                   "score_layer0": main_rep["score_layer0"],
+                   "score_layer0_meaning": "exact-match rows, correctly predicted experts, rows whose labels are all predicted, top-1 hits, out of T rows"},
+        "timing": main_rep["timing"],
         "roofline": main_rep["roofline"],
         "achievable": ceilings,
     }
@@ -266,7 +281,7 @@ def main():
     if args.sweep:
         also = []
         for T2 in list(w.decode_T) + [t for t in w.prefill_T if t != T]:
-            r2 = Runner(w, T2)
+            r2 = Runner(w, T2, k_pred=args.k_pred or None)
             rep = r2.report(max(args.steps, 50) if T2 <= 64 else args.steps, args.warmup)
             rep.pop("score_layer0")
             also.append(rep)

@@ -345,3 +345,49 @@ def test_paper_accuracy_definitions_on_a_worked_case():
     pred10 = np.array([[9, 4, 17, 30, 41, 62, 63, 1, 2, 3]], dtype=np.int32)
     assert oracle.score(pred6, true6, E).tolist() == [0, 5, 0, 1]
     assert oracle.score(pred10, true6, E).tolist() == [0, 6, 1, 1]
+
+
+# ---------------------------------------------------------------- activation profile (section 2.1)
+def test_activation_profile_entropy_closed_forms():
+    # uniform counts: entropy 1; a single active expert: 0; nothing counted or one expert: 0
+    for E in (2, 7, 64, 1000):
+        order, n, h = oracle.activation_profile(np.full(E, 5))
+        assert n == E and order.tolist() == list(range(E)) and abs(h - 1.0) < 1e-13          # a sum of E terms: rounding ~ E * 2^-53
+        one = np.zeros(E, dtype=np.int64); one[E // 2] = 9
+        order, n, h = oracle.activation_profile(one)
+        assert n == 1 and order[0] == E // 2 and (order[1:] == -1).all() and h == 0.0
+        assert oracle.activation_profile(np.zeros(E, dtype=np.int64))[1:] == (0, 0.0)
+    assert oracle.activation_profile(np.array([3]))[2] == 0.0
+    # m equally used experts out of E: ln m / ln E
+    c = np.zeros(16, dtype=np.int64); c[[1, 4, 9, 15]] = 7
+    assert abs(oracle.activation_profile(c)[2] - math.log(4) / math.log(16)) < 1e-14
+    # two experts with shares a and 1-a: the binary entropy function over ln 2
+    a = 3 / 8
+    want = -(a * math.log(a) + (1 - a) * math.log(1 - a)) / math.log(2)
+    assert abs(oracle.activation_profile(np.array([3, 5]))[2] - want) < 1e-14
+    # the skew the Phi-shaped workload plants (Zipf, s = 1.2) is well below the near-uniform 0.976 of the paper
+    z = np.round(1e6 / np.arange(1, 17) ** 1.2).astype(np.int64)
+    assert 0.5 < oracle.activation_profile(z)[2] < 0.9
+
+
+def test_activation_profile_order_by_brute_force_and_invariances():
+    g = np.random.default_rng(11)
+    for E in (1, 2, 5, 33, 257):
+        c = g.integers(0, 4, size=E) * g.integers(0, 3, size=E)          # many ties, many zeros
+        order, n, h = oracle.activation_profile(c)
+        # brute force: repeatedly take the largest remaining count, lowest id first
+        rest = {e: int(c[e]) for e in range(E) if c[e] > 0}
+        want = []
+        while rest:
+            best = max(rest.values())
+            e = min(k for k, v in rest.items() if v == best)
+            want.append(e); del rest[e]
+        assert order[:n].tolist() == want and (order[n:] == -1).all() and n == len(want)
+        # entropy ignores which expert holds which count, and the scale of the counts
+        perm = g.permutation(E)
+        assert abs(oracle.activation_profile(c[perm])[2] - h) < 1e-12
+        assert abs(oracle.activation_profile(c * 7)[2] - h) < 1e-12
+        # against the library routine for the same definition
+        if E > 1 and c.sum() > 0:
+            from scipy.stats import entropy as sp_entropy
+            assert abs(float(sp_entropy(c[c > 0] / c.sum())) / math.log(E) - h) < 1e-12
