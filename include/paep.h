@@ -165,6 +165,21 @@ paep_status paep_score(const int32_t *idx_dev, int32_t k_pred,
                        long long *counters_dev, void *stream);
 
 /*
+ * Expert popularity per layer from the activation counts that
+ * paep_group_by_expert produced (section 2.1: distribution of expert
+ * activation frequencies and its Shannon entropy; section 2.2.2: prefetching
+ * by expert popularity).  For every layer l:
+ *     order[l, 0..n_active[l]) = the experts with counts > 0 by descending
+ *                     count, equal counts by ascending id; the rest is -1
+ *     entropy[l]    = -sum_e p_e ln p_e / ln E,  p_e = counts[l,e] / sum_e counts[l,e],
+ *                     in double; 0 when E = 1 or the layer counted nothing
+ * counts_dev [L][E] int32 (negative entries count as 0), order_dev [L][E]
+ * int32, n_active_dev [L] int32, entropy_dev [L] double.  E <= PAEP_MAX_E.
+ */
+paep_status paep_activation_profile(const int32_t *counts_dev, int32_t L, int32_t E, int32_t *order_dev,
+                                    int32_t *n_active_dev, double *entropy_dev, void *stream);
+
+/*
  * Device ceilings, measured: not part of the paper's method.  The benchmark
  * runs them next to the predict kernels so that a roofline fraction can be
  * read against what this device sustains as well as against the published peak.

@@ -29,7 +29,7 @@ STATUS_NAMES = ["PAEP_OK", "PAEP_ERR_NULL", "PAEP_ERR_SHAPE", "PAEP_ERR_K", "PAE
 
 EXPORTS = ["paep_predict_workspace_bytes", "paep_predict_resolve_path", "paep_predict",
            "paep_group_workspace_bytes", "paep_group_by_expert", "paep_score",
-           "paep_probe_read", "paep_probe_mfma", "paep_status_string", "paep_version"]
+           "paep_activation_profile", "paep_probe_read", "paep_probe_mfma", "paep_status_string", "paep_version"]
 
 
 class PredictDesc(ctypes.Structure):
@@ -78,6 +78,8 @@ def lib() -> ctypes.CDLL:
         L.paep_group_by_expert.restype = ctypes.c_int
         L.paep_score.argtypes = [vp, i32, vp, i32, i32, i32, i32, vp, vp]
         L.paep_score.restype = ctypes.c_int
+        L.paep_activation_profile.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+        L.paep_activation_profile.restype = ctypes.c_int
         L.paep_probe_read.argtypes = [vp, sz, vp, sz, vp]
         L.paep_probe_read.restype = ctypes.c_int
         L.paep_probe_mfma.argtypes = [i32, i32, vp, sz, vp, ctypes.POINTER(ctypes.c_double)]
@@ -256,6 +258,30 @@ def score(idx: torch.Tensor, ref_idx: torch.Tensor, E: int, *, out: Optional[tor
     st = lib().paep_score(_ptr(idx), k_pred, _ptr(ref_idx), k_ref, L, T, E, _ptr(out), _stream_ptr(stream))
     if st != 0:
         raise PaepError(st, "paep_score")
+    return out
+
+
+class ActivationProfile(NamedTuple):
+    order: torch.Tensor       # [L, E] int32: experts by descending count, then -1
+    n_active: torch.Tensor    # [L] int32
+    entropy: torch.Tensor     # [L] float64: normalised Shannon entropy of the activation distribution
+
+
+def activation_profile(counts: torch.Tensor, stream=None) -> ActivationProfile:
+    """activation_profile(counts[L,E]) -> popularity-ordered expert list and entropy per layer."""
+    if counts.dim() == 1:
+        counts = counts.unsqueeze(0)
+    _need_device(counts)
+    if counts.dtype != torch.int32 or not counts.is_contiguous():
+        raise TypeError("counts must be contiguous int32")
+    L, E = counts.shape
+    out = ActivationProfile(torch.empty((L, E), dtype=torch.int32, device=counts.device),
+                            torch.empty((L,), dtype=torch.int32, device=counts.device),
+                            torch.empty((L,), dtype=torch.float64, device=counts.device))
+    st = lib().paep_activation_profile(_ptr(counts), L, E, _ptr(out.order), _ptr(out.n_active), _ptr(out.entropy),
+                                       _stream_ptr(stream))
+    if st != 0:
+        raise PaepError(st, "paep_activation_profile")
     return out
 
 

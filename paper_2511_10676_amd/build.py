@@ -17,7 +17,7 @@ OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpaep.so")
 
 SOURCES = ["paep_api.cpp", "predict_simple.hip", "predict_decode.hip", "predict_prefill.hip",
-           "group.hip", "score.hip", "probe.hip"]
+           "group.hip", "score.hip", "profile.hip", "probe.hip"]
 
 # packed fp32 vector ops are switched off for every device compile
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",

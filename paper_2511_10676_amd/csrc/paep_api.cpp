@@ -171,6 +171,16 @@ paep_status paep_score(const int32_t* idx_dev, int32_t k_pred, const int32_t* re
     return err == hipSuccess ? PAEP_OK : PAEP_ERR_HIP;
 }
 
+paep_status paep_activation_profile(const int32_t* counts_dev, int32_t L, int32_t E, int32_t* order_dev,
+                                    int32_t* n_active_dev, double* entropy_dev, void* stream)
+{
+    if (L < 1 || E < 1 || E > PAEP_MAX_E) return PAEP_ERR_SHAPE;
+    if (!counts_dev || !order_dev || !n_active_dev || !entropy_dev) return PAEP_ERR_NULL;
+    const hipError_t err = paep::launch_activation_profile(counts_dev, L, E, order_dev, n_active_dev, entropy_dev,
+                                                           static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? PAEP_OK : PAEP_ERR_HIP;
+}
+
 paep_status paep_probe_read(const void* src_dev, size_t bytes, void* sink_dev, size_t sink_bytes, void* stream)
 {
     if (!src_dev || !sink_dev) return PAEP_ERR_NULL;

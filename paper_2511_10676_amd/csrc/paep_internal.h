@@ -44,6 +44,9 @@ hipError_t launch_group(const int32_t* idx, int L, int T, int k, int E,
                         int32_t* active, int32_t* n_active, int32_t* n_invalid,
                         void* workspace, hipStream_t stream);
 
+hipError_t launch_activation_profile(const int32_t* counts, int L, int E, int32_t* order, int32_t* n_active,
+                                     double* entropy, hipStream_t stream);
+
 // device-ceiling probes
 static constexpr int PROBE_READ_GROUPS = 4096;
 hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t stream);

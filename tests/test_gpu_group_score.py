@@ -122,3 +122,31 @@ def test_toy_end_to_end_matches_oracle_and_golden():
     with open(os.path.join(os.path.dirname(__file__), "golden", "toy_oracle.json")) as f:
         gold = json.load(f)
     assert sc[0].cpu().numpy().tolist() == gold["score_k2_vs_ref"] == oracle.score(idx_ref, lay.ref, w.E).tolist()
+
+
+# ---------------------------------------------------------------- activation profile
+@pytest.mark.parametrize("E,L,T,k", [(1, 2, 50, 1), (2, 1, 100, 1), (16, 3, 4000, 2), (64, 4, 4096, 6), (257, 2, 900, 8),
+                                     (1024, 2, 3000, 16), (64, 2, 0, 6)])
+def test_activation_profile_matches_oracle(E, L, T, k):
+    g = np.random.default_rng(E * 5 + T)
+    idx = _skewed_idx(g, L, T, min(k, E), E) if T > 0 else np.zeros((L, 0, k), dtype=np.int32)
+    grp = B.group_by_expert(torch.from_numpy(idx).cuda(), E)
+    prof = B.activation_profile(grp.counts)
+    torch.cuda.synchronize()
+    for l in range(L):
+        counts = oracle.group_by_expert(idx[l], E)[0]
+        order, n_active, entropy = oracle.activation_profile(counts)
+        assert np.array_equal(prof.order[l].cpu().numpy(), order), f"order layer {l}"
+        assert int(prof.n_active[l]) == n_active
+        # both sides sum at most 1024 terms of magnitude < 1 in double, in different orders
+        assert abs(float(prof.entropy[l]) - entropy) <= 1e-12, f"entropy layer {l}"
+
+
+def test_activation_profile_ties_and_uniform():
+    c = torch.tensor([[5, 0, 5, 9, 0, 5, 9, 1], [3] * 8], dtype=torch.int32, device="cuda")
+    prof = B.activation_profile(c)
+    torch.cuda.synchronize()
+    assert prof.order[0].tolist() == [3, 6, 0, 2, 5, 7, -1, -1] and prof.n_active.tolist() == [6, 8]
+    assert prof.order[1].tolist() == list(range(8)) and abs(float(prof.entropy[1]) - 1.0) < 1e-13
+    want = oracle.activation_profile(c[0].cpu().numpy())
+    assert abs(float(prof.entropy[0]) - want[2]) <= 1e-12
