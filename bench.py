@@ -161,6 +161,9 @@ class Runner:
         self.i = 0                       # one untimed step on bank 0, whose weights the labels were drawn for
         self.step()
         self.torch.cuda.synchronize()
+        prof = self.B.activation_profile(self.grp.counts)          # untimed: popularity skew of what was just predicted
+        self.torch.cuda.synchronize()
+        self.entropy0 = round(float(prof.entropy[0]), 4)
         return {"T": T, "path": self.path, "ms_per_step": round(ms_step, 4),
                 "value": round(T * w.L / (ms_step * 1e-3), 1), "roofline": roof,
                 "score_layer0": self.counters[0].cpu().numpy().tolist(), "weight_banks": self.n_banks,
@@ -270,7 +273,7 @@ def main():
         "config": {"workload": f"{w.name}-shaped: L={w.L} d={w.d} r={w.r} E={w.E} k={w.k}, T={T} tokens/layer "
                                f"({main_rep['path']} path), step = predict + group_by_expert + score, all layers",
                    "k_pred": run.k_pred, "weight_banks": main_rep["weight_banks"],
-                   "score_layer0": main_rep["score_layer0"],
+                   "score_layer0": main_rep["score_layer0"], "activation_entropy_layer0": run.entropy0,
                    "score_layer0_meaning": "exact-match rows, correctly predicted experts, rows whose labels are all predicted, top-1 hits, out of T rows"},
         "timing": main_rep["timing"],
         "roofline": main_rep["roofline"],

@@ -239,7 +239,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     // registers beside the conversion's temporaries), so that their latency runs
     // under the rounding arithmetic; rows past E are clamped for the address and
     // zeroed by a select, which keeps the loads free of branches.
-    constexpr bool EARLY_W2 = (EB32 <= 4);
+    constexpr bool EARLY_W2 = (EB32 <= 4) && (MI * NI + EB32 * NI < 12);    // accumulators leave room for the fragments
     auto w2_fragment = [&](int eb, int unit0) {
         const int e = eb * 32 + l32;
         const uint16_t* wp = W2l + (long long)(e < E ? e : E - 1) * r + unit0;
