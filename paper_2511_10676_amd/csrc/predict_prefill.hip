@@ -2,22 +2,25 @@
 // linear layers of the predictor (paper section 4.3, eq. 3) fused into one
 // matrix-core kernel, with softmax and top-k (eq. 1, eq. 4) finished on chip.
 //
-// A workgroup (4 waves) owns BM = 128 tokens of one layer and walks the inner
-// width r in chunks of BN = 128 hidden units.  For a chunk it forms
+// A workgroup owns BM tokens of one layer and walks the inner width r in chunks
+// of BN hidden units (tile shapes: PfCfg below).  For a chunk it forms
 //     h^T[chunk, tokens] = W1[chunk, :] . x[tokens, :]^T
 // with v_mfma_f32_32x32x16_bf16, W1 rows as the A operand and token rows as
-// the B operand, both staged through double-buffered, padded LDS tiles of
-// BK = 64 along d.  The waves form a 2 x 2 grid over (hidden units, tokens),
-// 64 x 64 each.  Written this way round, the accumulator of a 32 x 32 block
-// holds, per lane, 16 hidden units of ONE token -- which is exactly what the B
-// operand of the next product needs -- so the chunk of h goes, after rounding
-// to bf16, bias and activation, straight from the accumulator registers into
+// the B operand, both copied global -> LDS without staging registers into a
+// ring of XOR-swizzled stages of BK elements along d.  The waves form a
+// WR x WT grid over (hidden units, tokens).  Written this way round, the
+// accumulator of a 32 x 32 block holds, per lane, 16 hidden units of ONE
+// token -- which is exactly what the B operand of the next product needs -- so
+// the chunk of h goes, after bias, activation and rounding to bf16, straight
+// from the accumulator registers into
 //     z^T[E, tokens] += W2[:, chunk] . h^T[chunk, tokens]
 // without touching LDS; only the W2 fragments are fetched (two 8-byte loads
 // per lane, matching the accumulator's row order).  h and z never reach HBM.
-// After the last chunk the two waves that share a token range add their
-// partial scores through LDS in a fixed order, and two lanes per token run
-// the softmax/top-k epilogue.
+// After the last chunk the waves that share a token range add their partial
+// scores through LDS in a fixed order, and one to four lanes per token run the
+// softmax/top-k epilogue.  r may also be split over several workgroups per
+// token tile; their partial score tiles then meet in a workspace and the
+// workgroup that finishes last adds them in a fixed order.
 #include <type_traits>
 
 #include "paep_device.h"
@@ -43,9 +46,9 @@ template <int N, class F> __device__ __forceinline__ void static_for(F&& f)
 //   BM tokens x BN hidden units per workgroup and chunk, BK elements of d per
 //   LDS tile, NS LDS stages; WR x WT waves over (hidden units, tokens); OCC
 //   workgroups per CU the register budget is sized for.
-// Tiles travel global -> LDS with global_load_lds_dwordx4 (no staging
-// registers), NS stages deep, so a tile is requested NS-1 iterations before it
-// is used.  An LDS tile row holds BK bf16 = CPR chunks of 16 bytes; chunk c of
+// Tiles travel global -> LDS with buffer_load_dwordx4 ... lds (no staging
+// registers), NS stages deep, so a tile is requested two or three iterations
+// before it is used.  An LDS tile row holds BK bf16 = CPR chunks of 16 bytes; chunk c of
 // row R sits in slot c ^ swz(R), chosen so that the 16-lane groups of a
 // ds_read_b128 touch 64 distinct banks.  The swizzle is applied on the global
 // side of the copy (a lane picks which chunk it fetches), because the LDS side
