@@ -32,24 +32,34 @@ MALL_BYTES = 256 << 20
 # dispatch, summed over the predict kernels), each scaled by what the counter
 # reads for the 1 GiB device copy of --copy-probe-mib in the same run (FETCH_SIZE
 # reads half the copied bytes: factor 2.0; WRITE_SIZE reads them exactly: 1.0).
-# Keyed by a hash of the kernel sources: once a kernel changes, the figure no
-# longer describes it and the report says null.
+# Keyed by a hash of the kernel sources (comments and blank space excluded):
+# once a kernel's code changes, the figure no longer describes it and the
+# report says null.
 TRAFFIC_BYTES = {
-    ("prefill", "dba6b20f4917e408"): {("deepseek_v2_lite", 4096): 3.854e9},
-    ("decode", "cea1189d733c4542"): {("deepseek_v2_lite", 1): 2.376e8, ("deepseek_v2_lite", 64): 3.085e8},
+    ("prefill", "2abac04b045c5712"): {("deepseek_v2_lite", 4096): 3.854e9},
+    ("decode", "78e1180e015cf4aa"): {("deepseek_v2_lite", 1): 2.376e8, ("deepseek_v2_lite", 64): 3.085e8},
 }
 
 
-def measured_traffic(path, workload, T):
+def _code_hash(path):
+    """Hash of the kernel's source with // comments and blank space removed, so that
+    rewording a comment does not retire a measurement but any change to code does."""
     import hashlib
+    import re
     m = hashlib.sha256()
     for f in ("predict_%s.hip" % path, "paep_device.h"):
         try:
-            with open(os.path.join(ROOT, "paper_2511_10676_amd", "csrc", f), "rb") as fh:
-                m.update(fh.read())
+            with open(os.path.join(ROOT, "paper_2511_10676_amd", "csrc", f), "r") as fh:
+                text = fh.read()
         except OSError:
             return None
-    return TRAFFIC_BYTES.get((path, m.hexdigest()[:16]), {}).get((workload, T))
+        text = re.sub(r"//[^\n]*", "", text)
+        m.update("".join(text.split()).encode())
+    return m.hexdigest()[:16]
+
+
+def measured_traffic(path, workload, T):
+    return TRAFFIC_BYTES.get((path, _code_hash(path)), {}).get((workload, T))
 
 
 def algorithmic_work(w, T, k=None):
