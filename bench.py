@@ -12,7 +12,8 @@ roofline of the dominant kernel (measured live with HIP events around the
 predict launches of the timed steps), and the CPU oracle timed on a bounded
 sample of the same workload (a baseline, not a target).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--T tokens] [--no-cpu] [--sweep]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--T tokens] [--k-pred K'] [--no-cpu]
+                    [--sweep] [--copy-probe-mib N]
 """
 import argparse
 import json
@@ -253,7 +254,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this library runs on one GPU; --gpus must be 1 (the path shards by tokens or layers "
-                 "with no communication in predict; see DESIGN.md)")
+                 "with no communication in predict)")
     import torch
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
