@@ -43,7 +43,7 @@ def lib() -> ctypes.CDLL:
         L.paep_oracle_predict.restype = c_i
         L.paep_oracle_group.argtypes = [c_p, c_i, c_i] + [c_p] * 6
         L.paep_oracle_group.restype = c_i
-        L.paep_oracle_score.argtypes = [c_p, c_i, c_p, c_i, c_i, c_i, c_p]
+        L.paep_oracle_score.argtypes = [c_p, c_i, c_p, c_i, c_i, c_i, c_p, c_p]
         L.paep_oracle_score.restype = c_i
         L.paep_oracle_num_threads.restype = c_i
         L.paep_oracle_round_bf16.argtypes = [ctypes.c_double]
@@ -112,15 +112,20 @@ def group_by_expert(idx, E: int):
     return counts, offsets, token_pos, active, int(n_active[0]), int(n_invalid[0])
 
 
-def score(idx, ref, E: int) -> np.ndarray:
-    """idx[T,k_pred], ref[T,k_ref] -> int64[4] = (n_exact, n_hit, n_cover, n_top1)."""
+def score(idx, ref, E: int, k_row=None) -> np.ndarray:
+    """idx[T,k_pred], ref[T,k_ref] -> int64[4] = (n_exact, n_hit, n_cover, n_top1).
+    k_row[T] (optional): row t uses only its first clamp(k_row[t], 1, k_pred) predicted ids."""
     idx = np.ascontiguousarray(idx, dtype=np.int32)
     ref = np.ascontiguousarray(ref, dtype=np.int32)
     if idx.ndim != 2 or ref.ndim != 2 or idx.shape[0] != ref.shape[0]:
         raise ValueError("idx and ref must be [T,k_pred] and [T,k_ref]")
     out = np.zeros(4, dtype=np.int64)
+    if k_row is not None:
+        k_row = np.ascontiguousarray(k_row, dtype=np.int32).reshape(-1)
+        if k_row.size != idx.shape[0]:
+            raise ValueError("k_row must have one entry per row")
     rc = lib().paep_oracle_score(_ptr(idx), idx.shape[1], _ptr(ref), ref.shape[1],
-                                 idx.shape[0], E, _ptr(out))
+                                 idx.shape[0], E, _ptr(k_row), _ptr(out))
     if rc != 0:
         raise ValueError("paep_oracle_score rejected its arguments")
     return out
@@ -157,3 +162,35 @@ def activation_profile(counts) -> Tuple[np.ndarray, int, float]:
                 h -= p * math.log(p)
         entropy = h / math.log(E)
     return order, len(ids), entropy
+
+
+def confidence_select(idx, probs, k_base: int, ratio: float):
+    """Confidence-driven over-provisioning of one layer (paper section 6, future work: rows predicted with high
+    confidence stay in exact-match mode, the others are over-provisioned).  The paper names no confidence
+    score; the one used here is the separation between the last expert of the exact-match set and the first
+    one outside it: row t is confident when probs[t, k_base-1] >= ratio * probs[t, k_base] (ratio = exp(tau)
+    for a margin tau between the two scores, since softmax shares one normaliser per row).  The comparison is
+    made in float32 -- one rounded product, one compare -- so that every implementation takes the same decision.
+
+    idx[T,kp] int32, probs[T,kp] float32 (descending), 1 <= k_base < kp ->
+        k_row[T]      k_base for confident rows, kp for the others
+        idx_out[T,kp] idx with the entries past k_row set to -1
+        n_wide        number of rows that were widened
+    """
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    probs = np.ascontiguousarray(probs, dtype=np.float32)
+    T, kp = idx.shape
+    if probs.shape != (T, kp) or not (1 <= k_base < kp):
+        raise ValueError("need idx, probs of one shape [T,kp] and 1 <= k_base < kp")
+    r32 = np.float32(ratio)
+    k_row = np.empty(T, dtype=np.int32)
+    idx_out = idx.copy()
+    n_wide = 0
+    for t in range(T):
+        confident = probs[t, k_base - 1] >= np.float32(r32 * probs[t, k_base])
+        k_row[t] = k_base if confident else kp
+        if confident:
+            idx_out[t, k_base:] = -1
+        else:
+            n_wide += 1
+    return k_row, idx_out, n_wide

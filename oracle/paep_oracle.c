@@ -224,9 +224,13 @@ int paep_oracle_group(const int32_t *idx, int n, int E,
  *   counters[2] n_cover  += (R subset of P) over-provisioning hit
  *   counters[3] n_top1   += (idx[t,0] in R) top-1
  * A row holding an id outside [0, E) in either array adds nothing.
+ * With k_row (may be NULL) row t uses only its first clamp(k_row[t], 1, k_pred)
+ * predicted ids: the per-row widths of confidence-driven over-provisioning
+ * (section 6, future work: confident rows in exact-match mode, the others
+ * over-provisioned).  Ids past that width are not looked at.
  */
 int paep_oracle_score(const int32_t *idx, int k_pred, const int32_t *ref, int k_ref,
-                      int T, int E, long long *counters)
+                      int T, int E, const int32_t *k_row, long long *counters)
 {
     if (T < 0 || E < 1 || k_pred < 1 || k_ref < 1 || !counters) return -1;
     if (T > 0 && (!idx || !ref)) return -1;
@@ -237,13 +241,15 @@ int paep_oracle_score(const int32_t *idx, int k_pred, const int32_t *ref, int k_
     for (int t = 0; t < T; ++t) {
         const int32_t *p = idx + (size_t)t * k_pred;
         const int32_t *q = ref + (size_t)t * k_ref;
+        int kp = k_pred;
+        if (k_row) { kp = k_row[t]; if (kp < 1) kp = 1; if (kp > k_pred) kp = k_pred; }
         int ok = 1;
-        for (int j = 0; j < k_pred; ++j) if (p[j] < 0 || p[j] >= E) ok = 0;
+        for (int j = 0; j < kp; ++j) if (p[j] < 0 || p[j] >= E) ok = 0;
         for (int j = 0; j < k_ref; ++j) if (q[j] < 0 || q[j] >= E) ok = 0;
         if (!ok) continue;
         memset(inP, 0, (size_t)E);
         memset(inR, 0, (size_t)E);
-        for (int j = 0; j < k_pred; ++j) inP[p[j]] = 1;
+        for (int j = 0; j < kp; ++j) inP[p[j]] = 1;
         for (int j = 0; j < k_ref; ++j) inR[q[j]] = 1;
         int nP = 0, nR = 0, both = 0;
         for (int e = 0; e < E; ++e) { nP += inP[e]; nR += inR[e]; both += (inP[e] & inR[e]); }

@@ -100,6 +100,11 @@ def test_decode_shared_tokens_across_layers():
 
 
 # ------------------------------------------------------------------ prefill path
+def test_prefill_shared_tokens_across_layers():
+    x, W1, W2, _, _ = _rand_layers(51, L=5, T=333, d=256, r=256, E=48, dtype="bf16")
+    _run_and_check(x[:1], W1, W2, None, None, 6, "bf16", path="prefill", what="prefill shared x")
+
+
 @pytest.mark.parametrize("T", [1, 127, 128, 300])
 def test_prefill_path_small(T):
     x, W1, W2, b1, b2 = _rand_layers(60 + T, L=2, T=T, d=256, r=256, E=64, dtype="bf16", bias=True)

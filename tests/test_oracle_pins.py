@@ -391,3 +391,56 @@ def test_activation_profile_order_by_brute_force_and_invariances():
         if E > 1 and c.sum() > 0:
             from scipy.stats import entropy as sp_entropy
             assert abs(float(sp_entropy(c[c > 0] / c.sum())) / math.log(E) - h) < 1e-12
+
+
+# ---------------------------------------------------------------- confidence-driven over-provisioning (section 6)
+def test_score_with_row_widths_against_sets_and_special_cases():
+    g = np.random.default_rng(21)
+    E, T, kp, kr = 24, 400, 7, 3
+    ref = np.stack([g.choice(E, kr, replace=False) for _ in range(T)]).astype(np.int32)
+    idx = np.stack([g.choice(E, kp, replace=False) for _ in range(T)]).astype(np.int32)
+    idx[::3, :kr] = ref[::3]                                   # a third of the rows predict the labels first
+    k_row = g.integers(-2, kp + 3, size=T).astype(np.int32)    # also out-of-range widths: clamped to [1, kp]
+    want = np.zeros(4, dtype=np.int64)
+    for t in range(T):
+        w = min(max(int(k_row[t]), 1), kp)
+        P, R = set(idx[t, :w].tolist()), set(ref[t].tolist())
+        want += [P == R, len(P & R), R <= P, idx[t, 0] in R]
+    assert oracle.score(idx, ref, E, k_row=k_row).tolist() == want.tolist()
+    # the full width is the plain score; a constant width is the score of the truncated prediction
+    assert oracle.score(idx, ref, E, k_row=np.full(T, kp)).tolist() == oracle.score(idx, ref, E).tolist()
+    assert oracle.score(idx, ref, E, k_row=np.full(T, kr)).tolist() == oracle.score(idx[:, :kr], ref, E).tolist()
+    # ids past a row's width are not looked at, even invalid ones
+    bad = idx.copy(); bad[:, kr:] = -1
+    assert oracle.score(bad, ref, E, k_row=np.full(T, kr)).tolist() == oracle.score(idx[:, :kr], ref, E).tolist()
+
+
+def test_confidence_select_hand_cases_and_monotonicity():
+    probs = np.array([[0.50, 0.30, 0.10, 0.05],     # p1/p2 = 3
+                      [0.40, 0.35, 0.15, 0.05],     # 2.333
+                      [0.30, 0.30, 0.30, 0.05],     # 1
+                      [0.60, 0.20, 0.19, 0.01]],    # 1.0526
+                     dtype=np.float32)
+    idx = np.arange(16, dtype=np.int32).reshape(4, 4)
+    k_row, out, n_wide = oracle.confidence_select(idx, probs, 2, 2.5)
+    assert k_row.tolist() == [2, 4, 4, 4] and n_wide == 3
+    assert out.tolist() == [[0, 1, -1, -1], [4, 5, 6, 7], [8, 9, 10, 11], [12, 13, 14, 15]]
+    # ratio 1: sorted probabilities always pass, nobody is widened; a huge ratio widens everybody
+    assert oracle.confidence_select(idx, probs, 2, 1.0)[0].tolist() == [2, 2, 2, 2]
+    assert oracle.confidence_select(idx, probs, 2, 1e30)[2] == 4
+    assert oracle.confidence_select(idx, probs, 1, 1.0)[0].tolist() == [1, 1, 1, 1]
+    # the number of widened rows never falls as the required separation grows; the decision equals the
+    # logit-margin rule z_a - z_b >= tau up to rounding (checked away from the boundary)
+    g = np.random.default_rng(22)
+    z = g.standard_normal((500, 16))
+    order = np.argsort(-z, axis=1)[:, :6]
+    zs = np.take_along_axis(z, order, axis=1)
+    p = (np.exp(zs) / np.exp(z).sum(axis=1, keepdims=True)).astype(np.float32)
+    last = -1
+    for tau in (0.0, 0.05, 0.2, 0.5, 1.0, 2.0):
+        k_row, _, n_wide = oracle.confidence_select(order.astype(np.int32), p, 3, math.exp(tau))
+        assert n_wide >= last
+        last = n_wide
+        gap = zs[:, 2] - zs[:, 3]
+        clear = np.abs(gap - tau) > 1e-4
+        assert np.array_equal((k_row == 3)[clear], (gap >= tau)[clear])
