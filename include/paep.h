@@ -165,6 +165,40 @@ paep_status paep_score(const int32_t *idx_dev, int32_t k_pred,
                        long long *counters_dev, void *stream);
 
 /*
+ * paep_score with a width per row: row (l, t) uses only its first
+ * clamp(k_row[l,t], 1, k_pred) predicted ids; ids past that width are not
+ * looked at (so the -1 padding paep_confidence_select writes is fine).
+ * k_row_dev is [L][T] int32.  Everything else as in paep_score.
+ */
+paep_status paep_score_rows(const int32_t *idx_dev, int32_t k_pred, const int32_t *k_row_dev,
+                            const int32_t *ref_dev, int32_t k_ref,
+                            int32_t L, int32_t T, int32_t E,
+                            long long *counters_dev, void *stream);
+
+/*
+ * Confidence-driven over-provisioning, the extension the paper's closing
+ * section sketches: rows predicted with high confidence are served in
+ * exact-match mode (k_base experts), the others are over-provisioned (all
+ * k_pred experts that paep_predict returned).  The paper fixes no confidence
+ * score; this one is the separation between the last expert inside the
+ * exact-match set and the first one outside it.  Row (l, t) is confident when
+ *     probs[l,t,k_base-1] >= ratio * probs[l,t,k_base]        (in float)
+ * i.e. ratio = exp(tau) asks for a margin tau between the two scores, because
+ * the softmax of one row shares one normaliser.  ratio >= 1.
+ *     k_row[l,t]      = k_base if confident, else k_pred
+ *     idx_out[l,t,j]  = idx[l,t,j] for j < k_row[l,t], else -1
+ *                       (paep_group_by_expert skips the -1 entries and counts
+ *                       them in n_invalid; idx_out must not overlap idx)
+ *     n_wide[l]       = number of rows of layer l that were widened
+ * idx_dev, idx_out_dev [L][T, k_pred] int32; probs_dev [L][T, k_pred] float as
+ * written by paep_predict (descending); k_row_dev [L][T] int32; n_wide_dev [L]
+ * int32.  1 <= k_base < k_pred <= PAEP_MAX_K.
+ */
+paep_status paep_confidence_select(const int32_t *idx_dev, const float *probs_dev,
+                                   int32_t L, int32_t T, int32_t k_pred, int32_t k_base, float ratio,
+                                   int32_t *idx_out_dev, int32_t *k_row_dev, int32_t *n_wide_dev, void *stream);
+
+/*
  * Expert popularity per layer from the activation counts that
  * paep_group_by_expert produced (section 2.1: distribution of expert
  * activation frequencies and its Shannon entropy; section 2.2.2: prefetching

@@ -29,7 +29,7 @@ STATUS_NAMES = ["PAEP_OK", "PAEP_ERR_NULL", "PAEP_ERR_SHAPE", "PAEP_ERR_K", "PAE
 
 EXPORTS = ["paep_predict_workspace_bytes", "paep_predict_resolve_path", "paep_predict",
            "paep_group_workspace_bytes", "paep_group_by_expert", "paep_score",
-           "paep_activation_profile", "paep_probe_read", "paep_probe_mfma", "paep_status_string", "paep_version"]
+           "paep_score_rows", "paep_confidence_select", "paep_activation_profile", "paep_probe_read", "paep_probe_mfma", "paep_status_string", "paep_version"]
 
 
 class PredictDesc(ctypes.Structure):
@@ -78,6 +78,10 @@ def lib() -> ctypes.CDLL:
         L.paep_group_by_expert.restype = ctypes.c_int
         L.paep_score.argtypes = [vp, i32, vp, i32, i32, i32, i32, vp, vp]
         L.paep_score.restype = ctypes.c_int
+        L.paep_score_rows.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, vp, vp]
+        L.paep_score_rows.restype = ctypes.c_int
+        L.paep_confidence_select.argtypes = [vp, vp, i32, i32, i32, i32, ctypes.c_float, vp, vp, vp, vp]
+        L.paep_confidence_select.restype = ctypes.c_int
         L.paep_activation_profile.argtypes = [vp, i32, i32, vp, vp, vp, vp]
         L.paep_activation_profile.restype = ctypes.c_int
         L.paep_probe_read.argtypes = [vp, sz, vp, sz, vp]
@@ -239,9 +243,10 @@ def group_by_expert(idx: torch.Tensor, E: int, *, out: Optional[Grouping] = None
     return out
 
 
-def score(idx: torch.Tensor, ref_idx: torch.Tensor, E: int, *, out: Optional[torch.Tensor] = None,
-          stream=None) -> torch.Tensor:
-    """score(idx[L,T,k_pred], ref_idx[L,T,k_ref]) -> int64 [L,4]: n_exact, n_hit, n_cover, n_top1."""
+def score(idx: torch.Tensor, ref_idx: torch.Tensor, E: int, *, k_row: Optional[torch.Tensor] = None,
+          out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """score(idx[L,T,k_pred], ref_idx[L,T,k_ref]) -> int64 [L,4]: n_exact, n_hit, n_cover, n_top1.
+    With k_row[L,T] (int32) each row uses only its first k_row predicted ids."""
     if idx.dim() == 2:
         idx = idx.unsqueeze(0)
     if ref_idx.dim() == 2:
@@ -255,9 +260,40 @@ def score(idx: torch.Tensor, ref_idx: torch.Tensor, E: int, *, out: Optional[tor
     k_ref = ref_idx.shape[2]
     if out is None:
         out = torch.empty((L, 4), dtype=torch.int64, device=idx.device)
-    st = lib().paep_score(_ptr(idx), k_pred, _ptr(ref_idx), k_ref, L, T, E, _ptr(out), _stream_ptr(stream))
+    if k_row is None:
+        st = lib().paep_score(_ptr(idx), k_pred, _ptr(ref_idx), k_ref, L, T, E, _ptr(out), _stream_ptr(stream))
+    else:
+        _need_device(k_row)
+        if k_row.dtype != torch.int32 or k_row.numel() != L * T or not k_row.is_contiguous():
+            raise TypeError("k_row must be contiguous int32 [L, T]")
+        st = lib().paep_score_rows(_ptr(idx), k_pred, _ptr(k_row), _ptr(ref_idx), k_ref, L, T, E, _ptr(out),
+                                   _stream_ptr(stream))
     if st != 0:
         raise PaepError(st, "paep_score")
+    return out
+
+
+class Widened(NamedTuple):
+    idx: torch.Tensor         # [L, T, k_pred] int32, -1 past each row's width
+    k_row: torch.Tensor       # [L, T] int32
+    n_wide: torch.Tensor      # [L] int32
+
+
+def confidence_select(idx: torch.Tensor, probs: torch.Tensor, k_base: int, ratio: float, stream=None) -> Widened:
+    """Keep k_base predictions on confident rows (probs[k_base-1] >= ratio * probs[k_base]), all of them elsewhere."""
+    if idx.dim() == 2:
+        idx, probs = idx.unsqueeze(0), probs.unsqueeze(0)
+    _need_device(idx, probs)
+    if idx.dtype != torch.int32 or probs.dtype != torch.float32 or idx.shape != probs.shape \
+            or not idx.is_contiguous() or not probs.is_contiguous():
+        raise TypeError("idx int32 and probs float32 must be contiguous and of one shape [L, T, k_pred]")
+    L, T, k_pred = idx.shape
+    out = Widened(torch.empty_like(idx), torch.empty((L, T), dtype=torch.int32, device=idx.device),
+                  torch.empty((L,), dtype=torch.int32, device=idx.device))
+    st = lib().paep_confidence_select(_ptr(idx), _ptr(probs), L, T, k_pred, k_base, float(ratio), _ptr(out.idx),
+                                      _ptr(out.k_row), _ptr(out.n_wide), _stream_ptr(stream))
+    if st != 0:
+        raise PaepError(st, "paep_confidence_select")
     return out
 
 

@@ -158,16 +158,46 @@ paep_status paep_group_by_expert(const int32_t* idx_dev, int32_t L, int32_t T, i
     return err == hipSuccess ? PAEP_OK : PAEP_ERR_HIP;
 }
 
-paep_status paep_score(const int32_t* idx_dev, int32_t k_pred, const int32_t* ref_dev, int32_t k_ref,
-                       int32_t L, int32_t T, int32_t E, long long* counters_dev, void* stream)
+static paep_status score_common(const int32_t* idx_dev, int32_t k_pred, const int32_t* k_row_dev,
+                                const int32_t* ref_dev, int32_t k_ref, int32_t L, int32_t T, int32_t E,
+                                long long* counters_dev, void* stream)
 {
     if (L < 1 || T < 0 || E < 1 || E > PAEP_MAX_E) return PAEP_ERR_SHAPE;
     if (k_pred < 1 || k_pred > PAEP_MAX_K || k_ref < 1 || k_ref > PAEP_MAX_K) return PAEP_ERR_K;
     if ((long long)T * L >= (1ll << 31)) return PAEP_ERR_SHAPE;
     if (!counters_dev) return PAEP_ERR_NULL;
     if (T > 0 && (!idx_dev || !ref_dev)) return PAEP_ERR_NULL;
-    const hipError_t err = paep::launch_score(idx_dev, k_pred, ref_dev, k_ref, L, T, E, counters_dev,
+    const hipError_t err = paep::launch_score(idx_dev, k_pred, ref_dev, k_ref, L, T, E, k_row_dev, counters_dev,
                                               static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? PAEP_OK : PAEP_ERR_HIP;
+}
+
+paep_status paep_score(const int32_t* idx_dev, int32_t k_pred, const int32_t* ref_dev, int32_t k_ref,
+                       int32_t L, int32_t T, int32_t E, long long* counters_dev, void* stream)
+{
+    return score_common(idx_dev, k_pred, nullptr, ref_dev, k_ref, L, T, E, counters_dev, stream);
+}
+
+paep_status paep_score_rows(const int32_t* idx_dev, int32_t k_pred, const int32_t* k_row_dev,
+                            const int32_t* ref_dev, int32_t k_ref, int32_t L, int32_t T, int32_t E,
+                            long long* counters_dev, void* stream)
+{
+    if (T > 0 && !k_row_dev) return PAEP_ERR_NULL;
+    return score_common(idx_dev, k_pred, k_row_dev, ref_dev, k_ref, L, T, E, counters_dev, stream);
+}
+
+paep_status paep_confidence_select(const int32_t* idx_dev, const float* probs_dev, int32_t L, int32_t T,
+                                   int32_t k_pred, int32_t k_base, float ratio, int32_t* idx_out_dev,
+                                   int32_t* k_row_dev, int32_t* n_wide_dev, void* stream)
+{
+    if (L < 1 || T < 0 || (long long)T * L >= (1ll << 31)) return PAEP_ERR_SHAPE;
+    if (k_pred < 2 || k_pred > PAEP_MAX_K || k_base < 1 || k_base >= k_pred) return PAEP_ERR_K;
+    if (!(ratio >= 1.0f)) return PAEP_ERR_SHAPE;             // also rejects NaN
+    if (!n_wide_dev) return PAEP_ERR_NULL;
+    if (T > 0 && (!idx_dev || !probs_dev || !idx_out_dev || !k_row_dev)) return PAEP_ERR_NULL;
+    const hipError_t err = paep::launch_confidence_select(idx_dev, probs_dev, L, T, k_pred, k_base, ratio,
+                                                          idx_out_dev, k_row_dev, n_wide_dev,
+                                                          static_cast<hipStream_t>(stream));
     return err == hipSuccess ? PAEP_OK : PAEP_ERR_HIP;
 }
 

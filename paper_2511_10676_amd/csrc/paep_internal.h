@@ -53,6 +53,9 @@ hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStrea
 hipError_t launch_probe_mfma(int groups, int iters, void* sink, hipStream_t stream);
 
 hipError_t launch_score(const int32_t* idx, int k_pred, const int32_t* ref, int k_ref,
-                        int L, int T, int E, long long* counters, hipStream_t stream);
+                        int L, int T, int E, const int32_t* k_row, long long* counters, hipStream_t stream);
+hipError_t launch_confidence_select(const int32_t* idx, const float* probs, int L, int T, int k_pred, int k_base,
+                                    float ratio, int32_t* idx_out, int32_t* k_row, int32_t* n_wide,
+                                    hipStream_t stream);
 
 }  // namespace paep

@@ -20,6 +20,14 @@ __global__ void score_clear_kernel(unsigned long long* counters, int n)
 // One token row: bitsets of the predicted and the labelled experts.  The row's
 // ids are fetched with independent loads (fixed trip count KM >= k) before any
 // is looked at, so a row costs one memory round trip.
+// Number of predicted ids row `row` uses: all k_pred, or its entry of k_row clamped to [1, k_pred].
+__device__ __forceinline__ int row_width(const int32_t* __restrict__ k_row, long long row, int k_pred)
+{
+    if (!k_row) return k_pred;
+    const int w = k_row[row];
+    return w < 1 ? 1 : (w > k_pred ? k_pred : w);
+}
+
 template <int KM>
 __device__ __forceinline__ void load_row(const int32_t* __restrict__ p, int k, int32_t (&v)[KM])
 {
@@ -76,16 +84,17 @@ __device__ __forceinline__ void score_vals(const int32_t (&pv)[KM], int k_pred, 
 template <int NW, int KM>
 __global__ __launch_bounds__(SCORE_THREADS) void score_kernel(
     const int32_t* __restrict__ idx, int k_pred, const int32_t* __restrict__ ref, int k_ref,
-    int T, int E, unsigned long long* __restrict__ counters)
+    int T, int E, const int32_t* __restrict__ k_row, unsigned long long* __restrict__ counters)
 {
     const int layer = blockIdx.y;
     const int t = blockIdx.x * SCORE_THREADS + threadIdx.x;
     int exact = 0, hit = 0, cover = 0, top1 = 0;
     if (t < T) {
         int32_t pv[KM], qv[KM];
-        load_row<KM>(idx + ((long long)layer * T + t) * k_pred, k_pred, pv);
+        const int kp = row_width(k_row, (long long)layer * T + t, k_pred);
+        load_row<KM>(idx + ((long long)layer * T + t) * k_pred, kp, pv);
         load_row<KM>(ref + ((long long)layer * T + t) * k_ref, k_ref, qv);
-        score_vals<NW, KM>(pv, k_pred, qv, k_ref, E, exact, hit, cover, top1);
+        score_vals<NW, KM>(pv, kp, qv, k_ref, E, exact, hit, cover, top1);
     }
     // wave reduction, then one atomic per wave and counter
     int packed_small = exact | (cover << 8) | (top1 << 16);    // each <= 64 after the reduction
@@ -113,7 +122,7 @@ static constexpr int LAYER_MAX_T = 1 << 12;
 template <int NW, int KM>
 __global__ __launch_bounds__(LAYER_THREADS) void score_layer_kernel(
     const int32_t* __restrict__ idx, int k_pred, const int32_t* __restrict__ ref, int k_ref,
-    int T, int E, unsigned long long* __restrict__ counters)
+    int T, int E, const int32_t* __restrict__ k_row, unsigned long long* __restrict__ counters)
 {
     __shared__ int part[LAYER_THREADS / 64][4];
     const int layer = blockIdx.x, tid = threadIdx.x;
@@ -122,17 +131,20 @@ __global__ __launch_bounds__(LAYER_THREADS) void score_layer_kernel(
     constexpr int RU = (KM <= 8) ? 4 : 1;
     for (int t0 = tid; t0 < T; t0 += LAYER_THREADS * RU) {
         int32_t pv[RU][KM], qv[RU][KM];
+        int kp[RU];
 #pragma unroll
         for (int u = 0; u < RU; ++u) {
             const int t = t0 + u * LAYER_THREADS;
+            kp[u] = k_pred;
             if (t < T) {
-                load_row<KM>(idx + ((long long)layer * T + t) * k_pred, k_pred, pv[u]);
+                kp[u] = row_width(k_row, (long long)layer * T + t, k_pred);
+                load_row<KM>(idx + ((long long)layer * T + t) * k_pred, kp[u], pv[u]);
                 load_row<KM>(ref + ((long long)layer * T + t) * k_ref, k_ref, qv[u]);
             }
         }
 #pragma unroll
         for (int u = 0; u < RU; ++u)
-            if (t0 + u * LAYER_THREADS < T) score_vals<NW, KM>(pv[u], k_pred, qv[u], k_ref, E, v[0], v[1], v[2], v[3]);
+            if (t0 + u * LAYER_THREADS < T) score_vals<NW, KM>(pv[u], kp[u], qv[u], k_ref, E, v[0], v[1], v[2], v[3]);
     }
 #pragma unroll
     for (int m = 1; m < 64; m <<= 1)
@@ -151,33 +163,83 @@ __global__ __launch_bounds__(LAYER_THREADS) void score_layer_kernel(
 
 template <int NW, int KM>
 static void launch_score_cfg(const int32_t* idx, int k_pred, const int32_t* ref, int k_ref, int L, int T, int E,
-                             unsigned long long* c, hipStream_t stream)
+                             const int32_t* k_row, unsigned long long* c, hipStream_t stream)
 {
     if (T <= LAYER_MAX_T) {
         hipLaunchKernelGGL((score_layer_kernel<NW, KM>), dim3(L), dim3(LAYER_THREADS), 0, stream, idx, k_pred, ref,
-                           k_ref, T, E, c);
+                           k_ref, T, E, k_row, c);
         return;
     }
     hipLaunchKernelGGL(score_clear_kernel, dim3((4 * L + 255) / 256), dim3(256), 0, stream, c, 4 * L);
     dim3 grid((T + SCORE_THREADS - 1) / SCORE_THREADS, L);
-    hipLaunchKernelGGL((score_kernel<NW, KM>), grid, dim3(SCORE_THREADS), 0, stream, idx, k_pred, ref, k_ref, T, E, c);
+    hipLaunchKernelGGL((score_kernel<NW, KM>), grid, dim3(SCORE_THREADS), 0, stream, idx, k_pred, ref, k_ref, T, E,
+                       k_row, c);
 }
 
 hipError_t launch_score(const int32_t* idx, int k_pred, const int32_t* ref, int k_ref,
-                        int L, int T, int E, long long* counters, hipStream_t stream)
+                        int L, int T, int E, const int32_t* k_row, long long* counters, hipStream_t stream)
 {
     unsigned long long* c = (unsigned long long*)counters;
     const bool small_k = k_pred <= 8 && k_ref <= 8;         // the interface allows up to 32 ids per row
     if (E <= 64) {
-        if (small_k) launch_score_cfg<1, 8>(idx, k_pred, ref, k_ref, L, T, E, c, stream);
-        else         launch_score_cfg<1, 32>(idx, k_pred, ref, k_ref, L, T, E, c, stream);
+        if (small_k) launch_score_cfg<1, 8>(idx, k_pred, ref, k_ref, L, T, E, k_row, c, stream);
+        else         launch_score_cfg<1, 32>(idx, k_pred, ref, k_ref, L, T, E, k_row, c, stream);
     } else if (E <= 256) {
-        if (small_k) launch_score_cfg<4, 8>(idx, k_pred, ref, k_ref, L, T, E, c, stream);
-        else         launch_score_cfg<4, 32>(idx, k_pred, ref, k_ref, L, T, E, c, stream);
+        if (small_k) launch_score_cfg<4, 8>(idx, k_pred, ref, k_ref, L, T, E, k_row, c, stream);
+        else         launch_score_cfg<4, 32>(idx, k_pred, ref, k_ref, L, T, E, k_row, c, stream);
     } else {
-        if (small_k) launch_score_cfg<16, 8>(idx, k_pred, ref, k_ref, L, T, E, c, stream);
-        else         launch_score_cfg<16, 32>(idx, k_pred, ref, k_ref, L, T, E, c, stream);
+        if (small_k) launch_score_cfg<16, 8>(idx, k_pred, ref, k_ref, L, T, E, k_row, c, stream);
+        else         launch_score_cfg<16, 32>(idx, k_pred, ref, k_ref, L, T, E, k_row, c, stream);
     }
+    return hipGetLastError();
+}
+
+// Confidence-driven over-provisioning (the paper's closing section proposes it
+// without fixing a confidence score; the one used here is documented in the C
+// header).  One thread per row: confident rows keep k_base predictions, the
+// others all k_pred; the entries past a row's width become -1 in idx_out.  The
+// decision is one fp32 product and one compare, so it is reproducible anywhere.
+__global__ __launch_bounds__(SCORE_THREADS) void confidence_select_kernel(
+    const int32_t* __restrict__ idx, const float* __restrict__ probs, long long rows, int T, int k_pred, int k_base,
+    float ratio, int32_t* __restrict__ idx_out, int32_t* __restrict__ k_row, int32_t* __restrict__ n_wide)
+{
+    const long long row = (long long)blockIdx.x * SCORE_THREADS + threadIdx.x;
+    int wide = 0;
+    if (row < rows) {
+        const float a = probs[row * k_pred + k_base - 1], b = probs[row * k_pred + k_base];
+        const bool confident = a >= __fmul_rn(ratio, b);
+        const int w = confident ? k_base : k_pred;
+        k_row[row] = w;
+        for (int j = 0; j < k_pred; ++j) idx_out[row * k_pred + j] = (j < w) ? idx[row * k_pred + j] : -1;
+        wide = !confident;
+    }
+    // rows of one wave may straddle two layers: count per lane's layer with ballots
+    const int layer = (row < rows) ? (int)(row / T) : -1;
+    const int first_layer = __shfl(layer, 0, 64);
+    const unsigned long long m0 = __ballot(wide && layer == first_layer);
+    const unsigned long long m1 = __ballot(wide && layer != first_layer);
+    if ((threadIdx.x & 63) == 0 && m0) atomicAdd(&n_wide[first_layer], __popcll(m0));
+    if (m1) {                                               // the wave crosses layer boundaries (T < 64): one atomic per row
+        if (wide && layer != first_layer) atomicAdd(&n_wide[layer], 1);
+    }
+}
+
+__global__ void clear_i32_kernel(int32_t* p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+hipError_t launch_confidence_select(const int32_t* idx, const float* probs, int L, int T, int k_pred, int k_base,
+                                    float ratio, int32_t* idx_out, int32_t* k_row, int32_t* n_wide,
+                                    hipStream_t stream)
+{
+    hipLaunchKernelGGL(clear_i32_kernel, dim3((L + 255) / 256), dim3(256), 0, stream, n_wide, L);
+    const long long rows = (long long)L * T;
+    if (rows > 0)
+        hipLaunchKernelGGL(confidence_select_kernel, dim3((unsigned)((rows + SCORE_THREADS - 1) / SCORE_THREADS)),
+                           dim3(SCORE_THREADS), 0, stream, idx, probs, rows, T, k_pred, k_base, ratio, idx_out, k_row,
+                           n_wide);
     return hipGetLastError();
 }
 

@@ -139,3 +139,22 @@ def test_binding_fails_loudly_without_the_library(monkeypatch):
     monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libpaep.so")
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         B.lib()
+
+
+def test_score_rows_and_confidence_select_reject_bad_arguments():
+    f = B.lib().paep_score_rows
+    assert f(FAKE, 2, None, FAKE, 2, 1, 4, 16, FAKE, None) == E_NULL          # widths missing
+    assert f(FAKE, 2, FAKE, FAKE, 2, 1, 4, 2000, FAKE, None) == E_SHAPE
+    assert f(FAKE, 0, FAKE, FAKE, 2, 1, 4, 16, FAKE, None) == E_K
+    assert f(None, 2, None, None, 2, 1, 0, 16, None, None) == E_NULL         # counters missing
+    g = B.lib().paep_confidence_select
+    import ctypes
+    r = ctypes.c_float
+    assert g(FAKE, FAKE, 1, 4, 6, 6, r(2.0), FAKE, FAKE, FAKE, None) == E_K      # k_base must be < k_pred
+    assert g(FAKE, FAKE, 1, 4, 6, 0, r(2.0), FAKE, FAKE, FAKE, None) == E_K
+    assert g(FAKE, FAKE, 1, 4, 1, 1, r(2.0), FAKE, FAKE, FAKE, None) == E_K
+    assert g(FAKE, FAKE, 1, 4, 6, 2, r(0.5), FAKE, FAKE, FAKE, None) == E_SHAPE  # ratio below 1
+    assert g(FAKE, FAKE, 1, 4, 6, 2, r(float("nan")), FAKE, FAKE, FAKE, None) == E_SHAPE
+    assert g(FAKE, FAKE, 0, 4, 6, 2, r(2.0), FAKE, FAKE, FAKE, None) == E_SHAPE
+    assert g(FAKE, None, 1, 4, 6, 2, r(2.0), FAKE, FAKE, FAKE, None) == E_NULL
+    assert g(FAKE, FAKE, 1, 4, 6, 2, r(2.0), FAKE, FAKE, None, None) == E_NULL

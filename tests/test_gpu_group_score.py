@@ -150,3 +150,52 @@ def test_activation_profile_ties_and_uniform():
     assert prof.order[1].tolist() == list(range(8)) and abs(float(prof.entropy[1]) - 1.0) < 1e-13
     want = oracle.activation_profile(c[0].cpu().numpy())
     assert abs(float(prof.entropy[0]) - want[2]) <= 1e-12
+
+
+# ---------------------------------------------------------------- confidence-driven over-provisioning
+def _sorted_softmax(g, L, T, kp, E, temp):
+    """Synthetic predictor output: the kp largest softmax values of random scores, and their experts."""
+    z = g.standard_normal((L, T, E)) * temp
+    order = np.argsort(-z, axis=2, kind="stable")[:, :, :kp]
+    zs = np.take_along_axis(z, order, axis=2)
+    p = np.exp(zs - z.max(axis=2, keepdims=True)) / np.exp(z - z.max(axis=2, keepdims=True)).sum(axis=2, keepdims=True)
+    return order.astype(np.int32), p.astype(np.float32)
+
+
+@pytest.mark.parametrize("L,T,E,kp,kb,kr,ratio", [
+    (2, 1, 16, 3, 2, 2, 1.5), (3, 50, 64, 10, 6, 6, 1.2), (2, 4097, 64, 10, 6, 6, 1.05), (1, 700, 128, 12, 8, 8, 1.0),
+    (4, 63, 16, 3, 2, 2, 3.0), (2, 300, 300, 32, 1, 5, 1.3), (2, 0, 64, 10, 6, 6, 1.2),
+])
+def test_confidence_select_group_and_score_match_oracle(L, T, E, kp, kb, kr, ratio):
+    g = np.random.default_rng(L * 1000 + T + kp)
+    idx, probs = _sorted_softmax(g, L, T, kp, E, temp=1.5) if T else (np.zeros((L, 0, kp), np.int32), np.zeros((L, 0, kp), np.float32))
+    ref = np.ascontiguousarray(idx[:, :, :kr]).copy()
+    if T:
+        flip = g.random((L, T)) < 0.3                        # some labels differ from the prediction's head
+        ref[flip, kr - 1] = idx[flip, kp - 1]
+    got = B.confidence_select(torch.from_numpy(idx).cuda(), torch.from_numpy(probs).cuda(), kb, ratio)
+    grp = B.group_by_expert(got.idx, E)
+    sc = B.score(got.idx, torch.from_numpy(ref).cuda(), E, k_row=got.k_row)
+    torch.cuda.synchronize()
+    for l in range(L):
+        k_row, idx_out, n_wide = oracle.confidence_select(idx[l], probs[l], kb, ratio)
+        assert np.array_equal(got.k_row[l].cpu().numpy(), k_row), f"k_row layer {l}"
+        assert np.array_equal(got.idx[l].cpu().numpy(), idx_out), f"idx_out layer {l}"
+        assert int(got.n_wide[l]) == n_wide
+        counts, offsets, pos, active, n_active, n_invalid = oracle.group_by_expert(idx_out, E)
+        assert np.array_equal(grp.counts[l].cpu().numpy(), counts) and np.array_equal(grp.token_pos[l].cpu().numpy(), pos)
+        assert int(grp.n_invalid[l]) == n_invalid == int((kp - k_row).sum())
+        assert sc[l].cpu().numpy().tolist() == oracle.score(idx_out, ref[l], E, k_row=k_row).tolist()
+
+
+def test_score_rows_with_arbitrary_widths():
+    g = np.random.default_rng(77)
+    L, T, E, kp, kr = 2, 5000, 64, 9, 4
+    idx = np.stack([[g.choice(E, kp, replace=False) for _ in range(T)] for _ in range(L)]).astype(np.int32)
+    ref = np.stack([[g.choice(E, kr, replace=False) for _ in range(T)] for _ in range(L)]).astype(np.int32)
+    ref[:, ::2] = idx[:, ::2, :kr]
+    k_row = g.integers(-1, kp + 2, size=(L, T)).astype(np.int32)
+    sc = B.score(torch.from_numpy(idx).cuda(), torch.from_numpy(ref).cuda(), E, k_row=torch.from_numpy(k_row).cuda())
+    torch.cuda.synchronize()
+    for l in range(L):
+        assert sc[l].cpu().numpy().tolist() == oracle.score(idx[l], ref[l], E, k_row=k_row[l]).tolist()
