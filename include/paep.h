@@ -114,7 +114,9 @@ int paep_predict_resolve_path(const paep_predict_desc *desc);
  *   idx_dev [L][T, k] int32  probs_dev [L][T, k] float
  *   logits_dev [L][T, E] float or NULL: the scores s, for checking only
  *   workspace_dev: at least paep_predict_workspace_bytes(desc) bytes,
- *                  16-byte aligned; may be NULL when that is 0.
+ *                  16-byte aligned; may be NULL when that is 0.  Contents on
+ *                  entry do not matter; calls that may run at the same time
+ *                  (different streams) need a workspace each.
  * x, W1, W2 and their layer strides must be 16-byte aligned.  With T = 0 the
  * token-sized arrays (x, idx, probs, logits) may be NULL.
  * Inputs must be finite; a NaN score orders below every number.
