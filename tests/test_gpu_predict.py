@@ -221,3 +221,41 @@ def test_stress_shaped_prefill_sampled_with_near_ties():
     assert lays[0].tie_rows.size == 328
     # the planted rows sit inside the tolerance band; they must still be valid selections
     assert tot.exempt > 0
+
+
+# ------------------------------------------------------------------ properties of the whole output at full size
+def _check_output_properties(out, E, k):
+    """What must hold for every row at any size: ids in range and distinct, probabilities positive,
+    descending, and no more than the whole softmax mass."""
+    idx, probs = out.idx, out.probs
+    assert bool(((idx >= 0) & (idx < E)).all())
+    srt = torch.sort(idx, dim=-1).values
+    assert bool((srt[..., 1:] != srt[..., :-1]).all()), "an expert selected twice in one row"
+    assert bool((probs > 0).all()) and bool(torch.isfinite(probs).all())
+    assert bool((probs[..., :-1] >= probs[..., 1:]).all()), "probabilities not in descending order"
+    assert float(probs.sum(dim=-1).max()) <= 1.0 + 1e-5
+
+
+@pytest.mark.parametrize("name,T", [("deepseek_v2_lite", 4096), ("deepseek_v2_lite", 64), ("qwen3_30b_a3b", 8192),
+                                    ("phi_mini_moe", 8192)])
+def test_full_size_outputs_have_the_required_properties_and_feed_grouping(name, T):
+    """All layers, the benchmark's launch configuration, random weights generated on the device; every row of the
+    output is checked for the properties above, and grouping/scoring of it for their conservation laws."""
+    w = configs.get(name)
+    g = torch.Generator(device="cuda"); g.manual_seed(7)
+    x = torch.randn((w.L, T, w.d), device="cuda", generator=g).to(torch.bfloat16)
+    W1 = (torch.randn((w.L, w.r, w.d), device="cuda", generator=g) / w.d ** 0.5).to(torch.bfloat16)
+    W2 = (torch.randn((w.L, w.E, w.r), device="cuda", generator=g) / w.r ** 0.5).to(torch.bfloat16)
+    out = B.predict(x, W1, W2, w.k)
+    torch.cuda.synchronize()
+    _check_output_properties(out, w.E, w.k)
+    grp = B.group_by_expert(out.idx, w.E)
+    sc = B.score(out.idx, out.idx, w.E)
+    torch.cuda.synchronize()
+    assert bool((grp.counts.sum(dim=1) == T * w.k).all()) and bool((grp.offsets[:, -1] == T * w.k).all())
+    assert bool((grp.n_invalid == 0).all())
+    # every position appears exactly once in a layer's token lists
+    pos = torch.sort(grp.token_pos, dim=1).values
+    assert bool((pos == torch.arange(T * w.k, device="cuda", dtype=torch.int32)[None, :]).all())
+    # a prediction scored against itself: every row exact, every expert a hit
+    assert sc.cpu().tolist() == [[T, T * w.k, T, T]] * w.L
