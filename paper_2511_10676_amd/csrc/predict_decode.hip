@@ -262,10 +262,12 @@ hipError_t launch_predict_decode(const PredictArgs& a)
                        (const uint16_t*)a.x, (const uint16_t*)a.W1, (const uint16_t*)a.W2,            \
                        (const uint16_t*)a.b1, partial)
     switch (TB) {
-    case 1: PAEP_LAUNCH_DEC(1, 4); break;
-    case 2: PAEP_LAUNCH_DEC(2, 4); break;
-    case 3: PAEP_LAUNCH_DEC(3, 2); break;
-    default: PAEP_LAUNCH_DEC(4, 2); break;
+    // load-batch depth by measurement: shallower batches need fewer registers, and the extra
+    // resident waves hide more latency than the deeper batches did
+    case 1: PAEP_LAUNCH_DEC(1, 2); break;
+    case 2: PAEP_LAUNCH_DEC(2, 2); break;
+    case 3: PAEP_LAUNCH_DEC(3, 1); break;
+    default: PAEP_LAUNCH_DEC(4, 1); break;
     }
 #undef PAEP_LAUNCH_DEC
     hipError_t err = hipGetLastError();
