@@ -541,14 +541,15 @@ __global__ void prefill_clear_tickets(int* tickets, int n)
 }
 
 // Configurations.  Big: 256 x 256 tiles, 8 waves, one workgroup per CU -- the
-// fewest bytes per flop through the CU's vector memory path, for E <= 64.
+// fewest bytes per flop through the CU's vector memory path, for E <= 64; five
+// stages of 32 KB fill the CU's 160 KB of LDS (three tiles of latency cover).
 // Mid: 256 tokens x 128 hidden units in 64-wide k tiles for 64 < E <= 128, waves
 // 2 x 4 (64 units x 64 tokens each: one LDS fragment read per matrix
 // instruction, 128 score accumulators per lane).  MidWide: the same tile with
 // the 8 waves side by side along tokens, which halves the score accumulators
 // per lane (E up to 256) at 1.25 fragment reads per matrix instruction.
 // Small: 128 x 128, 4 waves, any r that is a multiple of 128 and short inputs.
-typedef PfCfg<256, 256, 32, 4, 2, 4, 1> CfgBig;
+typedef PfCfg<256, 256, 32, 5, 2, 4, 1> CfgBig;
 typedef PfCfg<256, 128, 64, 3, 2, 4, 1> CfgMid;
 typedef PfCfg<256, 128, 64, 3, 1, 8, 1> CfgMidWide;
 typedef PfCfg<128, 128, 32, 4, 2, 2, 2> CfgSmall;
