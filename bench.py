@@ -245,7 +245,7 @@ def cpu_baseline(w, T, budget_s=20.0):
     import oracle
     from paper_2511_10676_amd import datagen
     mac_per_token = w.r * (w.d + w.E)
-    est_rate = 0.7e9 * oracle.num_threads()                 # MAC/s guess used only to size the sample
+    est_rate = 1.5e9 * oracle.num_threads()                 # MAC/s guess used only to size the sample (~15 s of work)
     tokens = int(max(1, min(T * w.L, budget_s * est_rate / mac_per_token)))
     layers = max(1, min(w.L, tokens // T)) if T <= tokens else 1
     Ts = min(T, tokens // layers)
