@@ -133,6 +133,12 @@ class Runner:
         self.sB = torch.cuda.Stream() if pipelined else self.sA
         self.ready = [torch.cuda.Event() for _ in range(nset)]
         self.done = [torch.cuda.Event() for _ in range(nset)]
+        # every call of a step is checked and marshalled once; the timed loop only enqueues
+        self.p_predict = [[B.prepare_predict(self.x, self.W1[b], self.W2[b], kp, b2=self.b2, out=self.outs[k],
+                                             workspace=self.ws) for k in range(nset)] for b in range(n_banks)]
+        self.p_group = [B.prepare_group_by_expert(self.outs[k].idx, w.E, out=self.grps[k], workspace=self.gwss[k])
+                        for k in range(nset)]
+        self.p_score = [B.prepare_score(self.outs[k].idx, self.ref, w.E, out=self.cnts[k]) for k in range(nset)]
         self.i = 0
         self.last = 0
 
@@ -147,16 +153,15 @@ class Runner:
                 self.sA.wait_event(self.done[k])          # the step that last used this buffer set is through
             if ev is not None:
                 ev[0].record()
-            B.predict(self.x, self.W1[bank], self.W2[bank], self.k_pred, b2=self.b2, out=self.outs[k],
-                      workspace=self.ws)
+            self.p_predict[bank][k]()
             if ev is not None:
                 ev[1].record()
             self.ready[k].record()
         with torch.cuda.stream(self.sB):
             if self.pipelined:
                 self.sB.wait_event(self.ready[k])
-            B.group_by_expert(self.outs[k].idx, w.E, out=self.grps[k], workspace=self.gwss[k])
-            B.score(self.outs[k].idx, self.ref, w.E, out=self.cnts[k])
+            self.p_group[k]()
+            self.p_score[k]()
             self.done[k].record()
             if ev is not None:
                 ev[2].record()

@@ -119,6 +119,23 @@ def _need_device(*tensors):
             raise ValueError("every tensor must be a contiguous device tensor")
 
 
+class Prepared:
+    """One library call with its arguments marshalled once.  Calling the object enqueues the work on
+    `stream` (default: torch's current stream) at the cost of a single foreign call -- for loops that
+    repeat the same call on the same buffers (a decode step per token)."""
+
+    __slots__ = ("_fn", "_name", "_args", "_keep", "result")
+
+    def __init__(self, fn, name, args, keep, result):
+        self._fn, self._name, self._args, self._keep, self.result = fn, name, args, keep, result
+
+    def __call__(self, stream=None):
+        st = self._fn(*self._args, _stream_ptr(stream))
+        if st != 0:
+            raise PaepError(st, self._name)
+        return self.result
+
+
 class Prediction(NamedTuple):
     idx: torch.Tensor                 # [L, T, k] int32
     probs: torch.Tensor               # [L, T, k] float32
@@ -143,17 +160,11 @@ def resolve_path(desc: PredictDesc) -> str:
     return PATH_NAME.get(p, "invalid")
 
 
-def predict(x: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, k: int, *,
-            b1: Optional[torch.Tensor] = None, b2: Optional[torch.Tensor] = None,
-            act: str = "none", path: str = "auto", want_logits: bool = False,
-            out: Optional[Prediction] = None, workspace: Optional[torch.Tensor] = None,
-            stream=None) -> Prediction:
-    """predict(x[L|1,T,d], W1[L,r,d], W2[L,E,r], k) -> idx[L,T,k], probs[L,T,k].
-
-    2-D inputs are taken as one layer.  x with a leading dimension of 1 (or
-    2-D x with 3-D weights) feeds the same tokens to every layer.  `out` and
-    `workspace` let a caller reuse buffers; otherwise they are allocated here.
-    """
+def prepare_predict(x: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, k: int, *,
+                    b1: Optional[torch.Tensor] = None, b2: Optional[torch.Tensor] = None,
+                    act: str = "none", path: str = "auto", want_logits: bool = False,
+                    out: Optional[Prediction] = None, workspace: Optional[torch.Tensor] = None) -> Prepared:
+    """Check and marshal one predict call; the returned object runs it (see `predict` for the arguments)."""
     if W1.dim() == 2:
         W1 = W1.unsqueeze(0)
     if W2.dim() == 2:
@@ -192,12 +203,25 @@ def predict(x: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, k: int, *,
     if workspace is None and need > 0:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    st = lib().paep_predict(ctypes.byref(desc), _ptr(x), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(b2),
-                            _ptr(idx), _ptr(probs), _ptr(logits), _ptr(workspace), ws_bytes,
-                            _stream_ptr(stream))
-    if st != 0:
-        raise PaepError(st, "paep_predict")
-    return Prediction(idx, probs, logits, resolve_path(desc))
+    args = (ctypes.byref(desc), _ptr(x), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(b2),
+            _ptr(idx), _ptr(probs), _ptr(logits), _ptr(workspace), ws_bytes)
+    return Prepared(lib().paep_predict, "paep_predict", args, (desc, x, W1, W2, b1, b2, workspace),
+                    Prediction(idx, probs, logits, resolve_path(desc)))
+
+
+def predict(x: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, k: int, *,
+            b1: Optional[torch.Tensor] = None, b2: Optional[torch.Tensor] = None,
+            act: str = "none", path: str = "auto", want_logits: bool = False,
+            out: Optional[Prediction] = None, workspace: Optional[torch.Tensor] = None,
+            stream=None) -> Prediction:
+    """predict(x[L|1,T,d], W1[L,r,d], W2[L,E,r], k) -> idx[L,T,k], probs[L,T,k].
+
+    2-D inputs are taken as one layer.  x with a leading dimension of 1 (or
+    2-D x with 3-D weights) feeds the same tokens to every layer.  `out` and
+    `workspace` let a caller reuse buffers; otherwise they are allocated here.
+    """
+    return prepare_predict(x, W1, W2, k, b1=b1, b2=b2, act=act, path=path, want_logits=want_logits, out=out,
+                           workspace=workspace)(stream)
 
 
 class Grouping(NamedTuple):
@@ -220,9 +244,9 @@ def alloc_grouping(L: int, T: int, k: int, E: int, device) -> Grouping:
                     torch.empty((L,), **i32), torch.empty((L,), **i32))
 
 
-def group_by_expert(idx: torch.Tensor, E: int, *, out: Optional[Grouping] = None,
-                    workspace: Optional[torch.Tensor] = None, stream=None) -> Grouping:
-    """group_by_expert(idx[L,T,k]) -> counts[L,E], offsets[L,E+1], token lists, prefetch list."""
+def prepare_group_by_expert(idx: torch.Tensor, E: int, *, out: Optional[Grouping] = None,
+                            workspace: Optional[torch.Tensor] = None) -> Prepared:
+    """Check and marshal one group_by_expert call; the returned object runs it."""
     if idx.dim() == 2:
         idx = idx.unsqueeze(0)
     _need_device(idx)
@@ -234,19 +258,20 @@ def group_by_expert(idx: torch.Tensor, E: int, *, out: Optional[Grouping] = None
     need = group_workspace_bytes(L, T, k, E)
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=idx.device)
-    st = lib().paep_group_by_expert(_ptr(idx), L, T, k, E, _ptr(out.counts), _ptr(out.offsets),
-                                    _ptr(out.token_pos), _ptr(out.active), _ptr(out.n_active),
-                                    _ptr(out.n_invalid), _ptr(workspace),
-                                    workspace.numel() * workspace.element_size(), _stream_ptr(stream))
-    if st != 0:
-        raise PaepError(st, "paep_group_by_expert")
-    return out
+    args = (_ptr(idx), L, T, k, E, _ptr(out.counts), _ptr(out.offsets), _ptr(out.token_pos), _ptr(out.active),
+            _ptr(out.n_active), _ptr(out.n_invalid), _ptr(workspace), workspace.numel() * workspace.element_size())
+    return Prepared(lib().paep_group_by_expert, "paep_group_by_expert", args, (idx, workspace), out)
 
 
-def score(idx: torch.Tensor, ref_idx: torch.Tensor, E: int, *, k_row: Optional[torch.Tensor] = None,
-          out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
-    """score(idx[L,T,k_pred], ref_idx[L,T,k_ref]) -> int64 [L,4]: n_exact, n_hit, n_cover, n_top1.
-    With k_row[L,T] (int32) each row uses only its first k_row predicted ids."""
+def group_by_expert(idx: torch.Tensor, E: int, *, out: Optional[Grouping] = None,
+                    workspace: Optional[torch.Tensor] = None, stream=None) -> Grouping:
+    """group_by_expert(idx[L,T,k]) -> counts[L,E], offsets[L,E+1], token lists, prefetch list."""
+    return prepare_group_by_expert(idx, E, out=out, workspace=workspace)(stream)
+
+
+def prepare_score(idx: torch.Tensor, ref_idx: torch.Tensor, E: int, *, k_row: Optional[torch.Tensor] = None,
+                  out: Optional[torch.Tensor] = None) -> Prepared:
+    """Check and marshal one score call; the returned object runs it."""
     if idx.dim() == 2:
         idx = idx.unsqueeze(0)
     if ref_idx.dim() == 2:
@@ -261,16 +286,21 @@ def score(idx: torch.Tensor, ref_idx: torch.Tensor, E: int, *, k_row: Optional[t
     if out is None:
         out = torch.empty((L, 4), dtype=torch.int64, device=idx.device)
     if k_row is None:
-        st = lib().paep_score(_ptr(idx), k_pred, _ptr(ref_idx), k_ref, L, T, E, _ptr(out), _stream_ptr(stream))
-    else:
-        _need_device(k_row)
-        if k_row.dtype != torch.int32 or k_row.numel() != L * T or not k_row.is_contiguous():
-            raise TypeError("k_row must be contiguous int32 [L, T]")
-        st = lib().paep_score_rows(_ptr(idx), k_pred, _ptr(k_row), _ptr(ref_idx), k_ref, L, T, E, _ptr(out),
-                                   _stream_ptr(stream))
-    if st != 0:
-        raise PaepError(st, "paep_score")
-    return out
+        return Prepared(lib().paep_score, "paep_score",
+                        (_ptr(idx), k_pred, _ptr(ref_idx), k_ref, L, T, E, _ptr(out)), (idx, ref_idx), out)
+    _need_device(k_row)
+    if k_row.dtype != torch.int32 or k_row.numel() != L * T or not k_row.is_contiguous():
+        raise TypeError("k_row must be contiguous int32 [L, T]")
+    return Prepared(lib().paep_score_rows, "paep_score_rows",
+                    (_ptr(idx), k_pred, _ptr(k_row), _ptr(ref_idx), k_ref, L, T, E, _ptr(out)),
+                    (idx, ref_idx, k_row), out)
+
+
+def score(idx: torch.Tensor, ref_idx: torch.Tensor, E: int, *, k_row: Optional[torch.Tensor] = None,
+          out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """score(idx[L,T,k_pred], ref_idx[L,T,k_ref]) -> int64 [L,4]: n_exact, n_hit, n_cover, n_top1.
+    With k_row[L,T] (int32) each row uses only its first k_row predicted ids."""
+    return prepare_score(idx, ref_idx, E, k_row=k_row, out=out)(stream)
 
 
 class Widened(NamedTuple):
