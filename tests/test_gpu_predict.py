@@ -259,3 +259,15 @@ def test_full_size_outputs_have_the_required_properties_and_feed_grouping(name, 
     assert bool((pos == torch.arange(T * w.k, device="cuda", dtype=torch.int32)[None, :]).all())
     # a prediction scored against itself: every row exact, every expert a hit
     assert sc.cpu().tolist() == [[T, T * w.k, T, T]] * w.L
+
+
+# ------------------------------------------------------------------ the smallest shapes each kernel family accepts
+@pytest.mark.parametrize("path,T,d,r,E,k,L", [
+    ("prefill", 1, 32, 128, 1, 1, 1), ("prefill", 3, 32, 128, 2, 2, 3), ("prefill", 129, 64, 256, 5, 5, 1),
+    ("prefill", 257, 32, 128, 33, 16, 2), ("decode", 1, 128, 64, 1, 1, 1), ("decode", 64, 128, 64, 3, 2, 2),
+    ("decode", 2, 128, 128, 512, 32, 1), ("simple", 1, 8, 8, 1, 1, 1), ("simple", 2, 16, 8, 3, 3, 2),
+])
+def test_smallest_shapes(path, T, d, r, E, k, L):
+    x, W1, W2, b1, b2 = _rand_layers(500 + T + E, L=L, T=T, d=d, r=r, E=E, dtype="bf16", bias=True, outliers=False)
+    out, *_ = _run_and_check(x, W1, W2, b1, b2, k, "bf16", path=path, what=f"smallest {path} T={T} d={d} r={r} E={E}")
+    assert out.path == path
