@@ -127,6 +127,23 @@ paep_status paep_predict(const paep_predict_desc *desc,
                          int32_t *idx_dev, float *probs_dev, float *logits_dev,
                          void *workspace_dev, size_t workspace_bytes, void *stream);
 
+/*
+ * paep_predict that also counts the selections: counts_dev[l][e] (int32,
+ * [L][E], required) is INCREASED by the number of tokens of layer l whose
+ * selection contains expert e -- the histogram paep_group_by_expert would
+ * compute, produced in the predictor's epilogue with integer atomics (exact,
+ * order-independent).  The caller zeroes counts_dev when a fresh histogram is
+ * wanted, or leaves it to accumulate expert popularity over calls, e.g. over
+ * the decode steps of a generation (the activation frequencies of section 2.1);
+ * paep_activation_profile turns it into a popularity order.  Everything else
+ * as in paep_predict.
+ */
+paep_status paep_predict_counted(const paep_predict_desc *desc,
+                                 const void *x_dev, const void *W1_dev, const void *W2_dev,
+                                 const void *b1_dev, const void *b2_dev,
+                                 int32_t *idx_dev, float *probs_dev, float *logits_dev, int32_t *counts_dev,
+                                 void *workspace_dev, size_t workspace_bytes, void *stream);
+
 /* Workspace bytes for paep_group_by_expert. */
 size_t paep_group_workspace_bytes(int32_t L, int32_t T, int32_t k, int32_t E);
 

@@ -27,7 +27,7 @@ MAX_K, MAX_E = 32, 1024
 STATUS_NAMES = ["PAEP_OK", "PAEP_ERR_NULL", "PAEP_ERR_SHAPE", "PAEP_ERR_K", "PAEP_ERR_DTYPE",
                 "PAEP_ERR_ALIGN", "PAEP_ERR_WORKSPACE", "PAEP_ERR_HIP", "PAEP_ERR_UNSUPPORTED"]
 
-EXPORTS = ["paep_predict_workspace_bytes", "paep_predict_resolve_path", "paep_predict",
+EXPORTS = ["paep_predict_workspace_bytes", "paep_predict_resolve_path", "paep_predict", "paep_predict_counted",
            "paep_group_workspace_bytes", "paep_group_by_expert", "paep_score",
            "paep_score_rows", "paep_confidence_select", "paep_activation_profile", "paep_probe_read", "paep_probe_mfma", "paep_status_string", "paep_version"]
 
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.paep_predict_resolve_path.restype = ctypes.c_int
         L.paep_predict.argtypes = [dp] + [vp] * 9 + [sz, vp]
         L.paep_predict.restype = ctypes.c_int
+        L.paep_predict_counted.argtypes = [dp] + [vp] * 10 + [sz, vp]
+        L.paep_predict_counted.restype = ctypes.c_int
         L.paep_group_workspace_bytes.argtypes = [i32] * 4
         L.paep_group_workspace_bytes.restype = sz
         L.paep_group_by_expert.argtypes = [vp] + [i32] * 4 + [vp] * 7 + [sz, vp]
@@ -163,7 +165,8 @@ def resolve_path(desc: PredictDesc) -> str:
 def prepare_predict(x: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, k: int, *,
                     b1: Optional[torch.Tensor] = None, b2: Optional[torch.Tensor] = None,
                     act: str = "none", path: str = "auto", want_logits: bool = False,
-                    out: Optional[Prediction] = None, workspace: Optional[torch.Tensor] = None) -> Prepared:
+                    out: Optional[Prediction] = None, workspace: Optional[torch.Tensor] = None,
+                    counts: Optional[torch.Tensor] = None) -> Prepared:
     """Check and marshal one predict call; the returned object runs it (see `predict` for the arguments)."""
     if W1.dim() == 2:
         W1 = W1.unsqueeze(0)
@@ -203,25 +206,34 @@ def prepare_predict(x: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, k: int,
     if workspace is None and need > 0:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    result = Prediction(idx, probs, logits, resolve_path(desc))
+    if counts is not None:
+        _need_device(counts)
+        if counts.dtype != torch.int32 or tuple(counts.shape) != (L, E):
+            raise ValueError("counts must be int32 [L, E]")
+        args = (ctypes.byref(desc), _ptr(x), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(b2),
+                _ptr(idx), _ptr(probs), _ptr(logits), _ptr(counts), _ptr(workspace), ws_bytes)
+        return Prepared(lib().paep_predict_counted, "paep_predict_counted", args,
+                        (desc, x, W1, W2, b1, b2, workspace, counts), result)
     args = (ctypes.byref(desc), _ptr(x), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(b2),
             _ptr(idx), _ptr(probs), _ptr(logits), _ptr(workspace), ws_bytes)
-    return Prepared(lib().paep_predict, "paep_predict", args, (desc, x, W1, W2, b1, b2, workspace),
-                    Prediction(idx, probs, logits, resolve_path(desc)))
+    return Prepared(lib().paep_predict, "paep_predict", args, (desc, x, W1, W2, b1, b2, workspace), result)
 
 
 def predict(x: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, k: int, *,
             b1: Optional[torch.Tensor] = None, b2: Optional[torch.Tensor] = None,
             act: str = "none", path: str = "auto", want_logits: bool = False,
             out: Optional[Prediction] = None, workspace: Optional[torch.Tensor] = None,
-            stream=None) -> Prediction:
+            counts: Optional[torch.Tensor] = None, stream=None) -> Prediction:
     """predict(x[L|1,T,d], W1[L,r,d], W2[L,E,r], k) -> idx[L,T,k], probs[L,T,k].
 
     2-D inputs are taken as one layer.  x with a leading dimension of 1 (or
     2-D x with 3-D weights) feeds the same tokens to every layer.  `out` and
     `workspace` let a caller reuse buffers; otherwise they are allocated here.
+    `counts` (int32 [L, E]) is increased by the activation counts of this call.
     """
     return prepare_predict(x, W1, W2, k, b1=b1, b2=b2, act=act, path=path, want_logits=want_logits, out=out,
-                           workspace=workspace)(stream)
+                           workspace=workspace, counts=counts)(stream)
 
 
 class Grouping(NamedTuple):

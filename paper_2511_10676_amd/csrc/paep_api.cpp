@@ -95,11 +95,11 @@ size_t paep_predict_workspace_bytes(const paep_predict_desc* desc)
     return 0;
 }
 
-paep_status paep_predict(const paep_predict_desc* desc,
-                         const void* x_dev, const void* W1_dev, const void* W2_dev,
-                         const void* b1_dev, const void* b2_dev,
-                         int32_t* idx_dev, float* probs_dev, float* logits_dev,
-                         void* workspace_dev, size_t workspace_bytes, void* stream)
+static paep_status predict_common(const paep_predict_desc* desc,
+                                  const void* x_dev, const void* W1_dev, const void* W2_dev,
+                                  const void* b1_dev, const void* b2_dev,
+                                  int32_t* idx_dev, float* probs_dev, float* logits_dev, int32_t* counts_dev,
+                                  void* workspace_dev, size_t workspace_bytes, void* stream)
 {
     const paep_status st = check_desc(desc);
     if (st != PAEP_OK) return st;
@@ -115,7 +115,7 @@ paep_status paep_predict(const paep_predict_desc* desc,
     if (desc->T == 0) return PAEP_OK;
 
     a.x = x_dev; a.W1 = W1_dev; a.W2 = W2_dev; a.b1 = b1_dev; a.b2 = b2_dev;
-    a.idx = idx_dev; a.probs = probs_dev; a.logits = logits_dev;
+    a.idx = idx_dev; a.probs = probs_dev; a.logits = logits_dev; a.counts = counts_dev;
     a.workspace = workspace_dev;
     a.stream = static_cast<hipStream_t>(stream);
     hipError_t err;
@@ -125,6 +125,27 @@ paep_status paep_predict(const paep_predict_desc* desc,
     default: err = paep::launch_predict_simple(a); break;
     }
     return err == hipSuccess ? PAEP_OK : PAEP_ERR_HIP;
+}
+
+paep_status paep_predict(const paep_predict_desc* desc,
+                         const void* x_dev, const void* W1_dev, const void* W2_dev,
+                         const void* b1_dev, const void* b2_dev,
+                         int32_t* idx_dev, float* probs_dev, float* logits_dev,
+                         void* workspace_dev, size_t workspace_bytes, void* stream)
+{
+    return predict_common(desc, x_dev, W1_dev, W2_dev, b1_dev, b2_dev, idx_dev, probs_dev, logits_dev, nullptr,
+                          workspace_dev, workspace_bytes, stream);
+}
+
+paep_status paep_predict_counted(const paep_predict_desc* desc,
+                                 const void* x_dev, const void* W1_dev, const void* W2_dev,
+                                 const void* b1_dev, const void* b2_dev,
+                                 int32_t* idx_dev, float* probs_dev, float* logits_dev, int32_t* counts_dev,
+                                 void* workspace_dev, size_t workspace_bytes, void* stream)
+{
+    if (!counts_dev) return PAEP_ERR_NULL;
+    return predict_common(desc, x_dev, W1_dev, W2_dev, b1_dev, b2_dev, idx_dev, probs_dev, logits_dev, counts_dev,
+                          workspace_dev, workspace_bytes, stream);
 }
 
 static paep_status check_group(int32_t L, int32_t T, int32_t k, int32_t E)

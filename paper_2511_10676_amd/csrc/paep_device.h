@@ -6,7 +6,9 @@
 //    lower expert id" (the tie rule of the C header),
 //  * a sorted top-K list kept in registers, filled by streaming over a row of
 //    scores and merged across the lanes that share a row with wave shuffles,
-//  * the softmax (eq. 1 of the paper) gathered at the selected experts.
+//  * the softmax (eq. 1 of the paper) gathered at the selected experts,
+//  * optionally, one integer atomic per selection into the layer's activation
+//    counts (the histogram that grouping would compute, fused into the epilogue).
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -101,7 +103,7 @@ struct TopList {
 // outputs j = g, g+G, ... < k.
 template <int KMAX, int G>
 __device__ __forceinline__ void row_softmax_topk(const float* zrow, int E, int k, int g,
-                                                 int32_t* idx_row, float* probs_row)
+                                                 int32_t* idx_row, float* probs_row, int32_t* counts_row)
 {
     TopList<KMAX> top;
     top.clear();
@@ -128,6 +130,7 @@ __device__ __forceinline__ void row_softmax_topk(const float* zrow, int E, int k
         if (j < k && (j % G) == g) {
             idx_row[j] = key_expert(top.key[j]);
             probs_row[j] = __expf(key_score(top.key[j]) - m) * inv;
+            if (counts_row) atomicAdd(&counts_row[key_expert(top.key[j])], 1);   // activation counts (exact: integers)
         }
     }
 }
@@ -135,12 +138,12 @@ __device__ __forceinline__ void row_softmax_topk(const float* zrow, int E, int k
 // Dispatch on the smallest list length that holds k.
 template <int G>
 __device__ __forceinline__ void row_softmax_topk_any(const float* zrow, int E, int k, int g,
-                                                     int32_t* idx_row, float* probs_row)
+                                                     int32_t* idx_row, float* probs_row, int32_t* counts_row)
 {
-    if (k <= 2)       row_softmax_topk<2, G>(zrow, E, k, g, idx_row, probs_row);
-    else if (k <= 8)  row_softmax_topk<8, G>(zrow, E, k, g, idx_row, probs_row);
-    else if (k <= 16) row_softmax_topk<16, G>(zrow, E, k, g, idx_row, probs_row);
-    else              row_softmax_topk<32, G>(zrow, E, k, g, idx_row, probs_row);
+    if (k <= 2)       row_softmax_topk<2, G>(zrow, E, k, g, idx_row, probs_row, counts_row);
+    else if (k <= 8)  row_softmax_topk<8, G>(zrow, E, k, g, idx_row, probs_row, counts_row);
+    else if (k <= 16) row_softmax_topk<16, G>(zrow, E, k, g, idx_row, probs_row, counts_row);
+    else              row_softmax_topk<32, G>(zrow, E, k, g, idx_row, probs_row, counts_row);
 }
 
 // Softmax + top-k of one row held in registers by a whole wave: lane l owns
@@ -150,7 +153,7 @@ __device__ __forceinline__ void row_softmax_topk_any(const float* zrow, int E, i
 // butterflies, so the result does not depend on scheduling.
 template <int NV>
 __device__ __forceinline__ void wave_softmax_topk(const float (&z)[NV], int E, int k, int lane,
-                                                  int32_t* idx_row, float* probs_row)
+                                                  int32_t* idx_row, float* probs_row, int32_t* counts_row)
 {
     uint64_t key[NV];
 #pragma unroll
@@ -184,17 +187,18 @@ __device__ __forceinline__ void wave_softmax_topk(const float (&z)[NV], int E, i
     if (lane < k) {
         idx_row[lane] = key_expert(mine);
         probs_row[lane] = __expf(key_score(mine) - m) / s;
+        if (counts_row) atomicAdd(&counts_row[key_expert(mine)], 1);
     }
 }
 
 // Same, for kernels that only accept k <= 16 (keeps their register budget small).
 template <int G>
 __device__ __forceinline__ void row_softmax_topk_upto16(const float* zrow, int E, int k, int g,
-                                                        int32_t* idx_row, float* probs_row)
+                                                        int32_t* idx_row, float* probs_row, int32_t* counts_row)
 {
-    if (k <= 2)      row_softmax_topk<2, G>(zrow, E, k, g, idx_row, probs_row);
-    else if (k <= 8) row_softmax_topk<8, G>(zrow, E, k, g, idx_row, probs_row);
-    else             row_softmax_topk<16, G>(zrow, E, k, g, idx_row, probs_row);
+    if (k <= 2)      row_softmax_topk<2, G>(zrow, E, k, g, idx_row, probs_row, counts_row);
+    else if (k <= 8) row_softmax_topk<8, G>(zrow, E, k, g, idx_row, probs_row, counts_row);
+    else             row_softmax_topk<16, G>(zrow, E, k, g, idx_row, probs_row, counts_row);
 }
 
 }  // namespace paep

@@ -20,6 +20,7 @@ struct PredictArgs {
     int32_t* idx;
     float* probs;
     float* logits;      // nullable
+    int32_t* counts;    // nullable: [L][E] activation counts, added to
     void* workspace;
     hipStream_t stream;
 };

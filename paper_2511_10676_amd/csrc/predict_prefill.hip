@@ -85,7 +85,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ W1, const uint16_t* __restrict__ W2,
     const uint16_t* __restrict__ b1, const uint16_t* __restrict__ b2,
     int32_t* __restrict__ idx, float* __restrict__ probs, float* __restrict__ logits,
-    float* __restrict__ zpart, int* __restrict__ tickets)
+    float* __restrict__ zpart, int* __restrict__ tickets, int32_t* __restrict__ counts)
 {
     constexpr int BM = C::BM, BN = C::BN, BK = C::BK, NS = C::NS, WR = C::WR, WT = C::WT;
     constexpr int WM = C::WM, WN = C::WN, MI = C::MI, NI = C::NI, CPR = C::CPR, RPI = C::RPI;
@@ -466,7 +466,8 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
         // the lanes of a group take the same branch (same token)
         if (tbase + tl < T) {
             const long long row = (long long)layer * T + tbase + tl;
-            row_softmax_topk_upto16<ZG>(zs + tl * ZP, E, k, gg, idx + row * k, probs + row * k);
+            row_softmax_topk_upto16<ZG>(zs + tl * ZP, E, k, gg, idx + row * k, probs + row * k,
+                                        counts ? counts + (long long)layer * E : nullptr);
         }
         __syncthreads();
     };
@@ -626,7 +627,7 @@ static hipError_t launch_cfg(const PredictArgs& a)
     hipLaunchKernelGGL(kern, dim3(total), dim3(C::THREADS), lds, a.stream, a.T, a.d, a.r, a.E, a.k, a.act, tiles,
                        total, groups, cpg, a.x_stride, a.w1_stride, a.w2_stride, (const uint16_t*)a.x,
                        (const uint16_t*)a.W1, (const uint16_t*)a.W2, (const uint16_t*)a.b1,
-                       (const uint16_t*)a.b2, a.idx, a.probs, a.logits, zpart, tickets);
+                       (const uint16_t*)a.b2, a.idx, a.probs, a.logits, zpart, tickets, a.counts);
     return hipGetLastError();
 }
 

@@ -158,3 +158,10 @@ def test_score_rows_and_confidence_select_reject_bad_arguments():
     assert g(FAKE, FAKE, 0, 4, 6, 2, r(2.0), FAKE, FAKE, FAKE, None) == E_SHAPE
     assert g(FAKE, None, 1, 4, 6, 2, r(2.0), FAKE, FAKE, FAKE, None) == E_NULL
     assert g(FAKE, FAKE, 1, 4, 6, 2, r(2.0), FAKE, FAKE, None, None) == E_NULL
+
+
+def test_counted_predict_needs_its_counts():
+    d = _desc(T=4)
+    f = B.lib().paep_predict_counted
+    assert f(ctypes.byref(d), FAKE, FAKE, FAKE, None, None, FAKE, FAKE, None, None, FAKE, 1 << 30, None) == E_NULL
+    assert f(ctypes.byref(_desc(T=4, k=0)), FAKE, FAKE, FAKE, None, None, FAKE, FAKE, None, FAKE, FAKE, 1 << 30, None) == E_K

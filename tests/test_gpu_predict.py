@@ -9,6 +9,7 @@ import torch
 from paper_2511_10676_amd import binding as B
 from paper_2511_10676_amd import configs, datagen
 
+import oracle
 import parity
 
 pytestmark = pytest.mark.gpu
@@ -271,3 +272,30 @@ def test_smallest_shapes(path, T, d, r, E, k, L):
     x, W1, W2, b1, b2 = _rand_layers(500 + T + E, L=L, T=T, d=d, r=r, E=E, dtype="bf16", bias=True, outliers=False)
     out, *_ = _run_and_check(x, W1, W2, b1, b2, k, "bf16", path=path, what=f"smallest {path} T={T} d={d} r={r} E={E}")
     assert out.path == path
+
+
+# ------------------------------------------------------------------ activation counts from the predictor's epilogue
+@pytest.mark.parametrize("path,T,d,r,E,k,L,dtype", [
+    ("simple", 37, 72, 40, 13, 5, 2, "f32"), ("decode", 7, 256, 128, 40, 8, 3, "bf16"),
+    ("decode", 64, 256, 128, 250, 12, 2, "bf16"), ("prefill", 300, 128, 384, 64, 6, 2, "bf16"),
+    ("prefill", 700, 128, 256, 200, 16, 3, "bf16"), ("prefill", 8300, 64, 512, 64, 6, 4, "bf16"),
+])
+def test_counted_predict_adds_the_histogram_of_its_selections(path, T, d, r, E, k, L, dtype):
+    x, W1, W2, _, _ = _rand_layers(900 + T, L=L, T=T, d=d, r=r, E=E, dtype=dtype)
+    xs, a, b = _dev(x, dtype), _dev(W1, dtype), _dev(W2, dtype)
+    plain = B.predict(xs, a, b, k, path=path)
+    counts = torch.full((L, E), 3, dtype=torch.int32, device="cuda")          # not zero: the call adds
+    out = B.predict(xs, a, b, k, path=path, counts=counts)
+    out2 = B.predict(xs, a, b, k, path=path, counts=counts)                   # accumulates over calls
+    torch.cuda.synchronize()
+    assert out.path == path
+    assert torch.equal(out.idx, plain.idx) and torch.equal(out.probs, plain.probs) and torch.equal(out2.idx, plain.idx)
+    for l in range(L):
+        hist = torch.bincount(out.idx[l].flatten().to(torch.int64), minlength=E).to(torch.int32)
+        assert torch.equal(counts[l], 3 + 2 * hist), f"layer {l}"
+    # against the oracle where selection is unambiguous (fp32: every row is strict)
+    if dtype == "f32":
+        for l in range(L):
+            idx_o, _, _ = oracle.predict(x[l], W1[l], W2[l], k, want_logits=False)
+            want = oracle.group_by_expert(idx_o, E)[0]
+            assert np.array_equal((counts[l].cpu().numpy() - 3) // 2, want)
