@@ -39,8 +39,8 @@ MALL_BYTES = 256 << 20
 # once a kernel's code changes, the figure no longer describes it and the
 # report says null.
 TRAFFIC_BYTES = {
-    ("prefill", "79bbb68da66c2edc"): {("deepseek_v2_lite", 4096): 3.849e+09},
-    ("decode", "5a6b9f0f78cde582"): {("deepseek_v2_lite", 1): 2.382e+08, ("deepseek_v2_lite", 64): 3.238e+08},
+    ("prefill", "16b68d203279d966"): {("deepseek_v2_lite", 4096): 3.847e+09},
+    ("decode", "18bfb2d8d07fe899"): {("deepseek_v2_lite", 1): 2.382e+08, ("deepseek_v2_lite", 64): 3.241e+08},
 }
 
 
