@@ -640,7 +640,7 @@ static int pick_cfg(const PredictArgs& a)
 {
     const bool large = enough_large_tiles(a);
     if (a.E <= 64) return (large && a.r % 256 == 0) ? 2 : 0;
-    return large ? 3 : 1;
+    return (large && a.d % 64 == 0) ? 3 : 1;                  // the mid configurations walk d in steps of 64
 }
 
 size_t prefill_workspace_bytes(const PredictArgs& a)

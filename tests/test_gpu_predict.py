@@ -162,6 +162,8 @@ def test_empty_call():
     (64, 6, 512, 4096, 4, 8300), (200, 8, 256, 4096, 4, 8300),
     # several chunks of r per tile, many layers, a single layer with many tiles
     (64, 6, 768, 64, 4, 8229), (64, 6, 1024, 64, 16, 8229), (128, 8, 640, 64, 9, 8229), (16, 2, 1280, 32, 1, 33000),
+    # more than 64 experts with d not a multiple of 64: the 64-wide-tile configurations must not be chosen
+    (128, 8, 256, 96, 4, 8229), (200, 8, 256, 32, 4, 8229),
 ])
 def test_prefill_large_tile_configs_with_ragged_tail(E, k, r, d, L, T):
     """Enough tokens that the large-tile kernels are chosen, a token count that
