@@ -544,6 +544,8 @@ __global__ void prefill_clear_tickets(int* tickets, int n)
 // Configurations.  Big: 256 x 256 tiles, 8 waves, one workgroup per CU -- the
 // fewest bytes per flop through the CU's vector memory path, for E <= 64; five
 // stages of 32 KB fill the CU's 160 KB of LDS (three tiles of latency cover).
+// BigDeep: the same tile in two 64-wide stages, measured +3% at d = 4096 and
+// no better at d = 2048.
 // Mid: 256 tokens x 128 hidden units in 64-wide k tiles for 64 < E <= 128, waves
 // 2 x 4 (64 units x 64 tokens each: one LDS fragment read per matrix
 // instruction, 128 score accumulators per lane).  MidWide: the same tile with
@@ -551,6 +553,7 @@ __global__ void prefill_clear_tickets(int* tickets, int n)
 // per lane (E up to 256) at 1.25 fragment reads per matrix instruction.
 // Small: 128 x 128, 4 waves, any r that is a multiple of 128 and short inputs.
 typedef PfCfg<256, 256, 32, 5, 2, 4, 1> CfgBig;
+typedef PfCfg<256, 256, 64, 2, 2, 4, 1> CfgBigDeep;      // long rows (d >= 4096): half as many barriers per flop
 typedef PfCfg<256, 128, 64, 3, 2, 4, 1> CfgMid;
 typedef PfCfg<256, 128, 64, 3, 1, 8, 1> CfgMidWide;
 typedef PfCfg<128, 128, 32, 4, 2, 2, 2> CfgSmall;
@@ -656,7 +659,9 @@ size_t prefill_workspace_bytes(const PredictArgs& a)
 hipError_t launch_predict_prefill(const PredictArgs& a)
 {
     switch (pick_cfg(a)) {
-    case 2: return a.E <= 32 ? launch_cfg<CfgBig, 1>(a) : launch_cfg<CfgBig, 2>(a);
+    case 2:
+        if (a.d >= 4096 && a.d % 64 == 0) return a.E <= 32 ? launch_cfg<CfgBigDeep, 1>(a) : launch_cfg<CfgBigDeep, 2>(a);
+        return a.E <= 32 ? launch_cfg<CfgBig, 1>(a) : launch_cfg<CfgBig, 2>(a);
     case 3: return a.E <= 128 ? launch_cfg<CfgMid, 4>(a) : launch_cfg<CfgMidWide, 8>(a);
     case 1: return a.E <= 128 ? launch_cfg<CfgSmallWide, 4>(a) : launch_cfg<CfgSmallWide, 8>(a);
     default: return a.E <= 32 ? launch_cfg<CfgSmall, 1>(a) : launch_cfg<CfgSmall, 2>(a);
