@@ -64,6 +64,16 @@ typedef enum {
     PAEP_PATH_PREFILL = 3     /* bf16, large T: fused back-to-back matrix-core tiles */
 } paep_path;
 
+/* What paep_predict writes to probs for the selected experts.  The paper's
+ * predictor is trained through a sigmoid (binary cross-entropy per expert,
+ * section 4.4) while the router it imitates normalises with a softmax (eq. 1);
+ * its closing section asks for per-prediction confidence scores.  All three
+ * are monotone in the score, so the selection is the same.
+ *   SOFTMAX_ALL   softmax over all E scores, gathered at the selection
+ *   SOFTMAX_TOPK  softmax over the k selected scores only (sums to 1 per row)
+ *   SIGMOID       1 / (1 + exp(-s)) of each selected score                    */
+typedef enum { PAEP_PROB_SOFTMAX_ALL = 0, PAEP_PROB_SOFTMAX_TOPK = 1, PAEP_PROB_SIGMOID = 2 } paep_prob;
+
 #define PAEP_MAX_K 32
 #define PAEP_MAX_E 1024
 
@@ -83,7 +93,7 @@ typedef struct {
     int32_t dtype;      /* paep_dtype of x, W1, W2, b1, b2 */
     int32_t act;        /* paep_act */
     int32_t path;       /* paep_path */
-    int32_t reserved;   /* must be 0 */
+    int32_t prob;       /* paep_prob; 0 = softmax over all E */
     int64_t x_layer_stride;
     int64_t w1_layer_stride;
     int64_t w2_layer_stride;
@@ -104,7 +114,8 @@ int paep_predict_resolve_path(const paep_predict_desc *desc);
  *     s = W2_l h   (+ b2_l)                      scores, fp32
  *     idx[l,t,:]   = the k experts with the highest s, in descending score
  *                    order, equal scores by ascending expert id
- *     probs[l,t,j] = softmax(s)[idx[l,t,j]]      over all E scores
+ *     probs[l,t,j] = softmax(s)[idx[l,t,j]]      over all E scores (desc->prob = 0;
+ *                    see paep_prob for the other two confidence scores)
  * Selection is done on the raw scores: softmax preserves ranking
  * (sections 1 and 3.1).  h and s never go to memory unless logits_dev is
  * given.
@@ -144,7 +155,59 @@ paep_status paep_predict_counted(const paep_predict_desc *desc,
                                  int32_t *idx_dev, float *probs_dev, float *logits_dev, int32_t *counts_dev,
                                  void *workspace_dev, size_t workspace_bytes, void *stream);
 
-/* Workspace bytes for paep_group_by_expert. */
+/*
+ * paep_predict with the confidence outputs the paper's closing section asks
+ * for (prediction confidence scores that drive dynamic over-provisioning):
+ *   margin_dev [L][T] float, nullable: for every row, the score of the last
+ *       selected expert minus the best score that was left out,
+ *       s(k-th) - s((k+1)-th) >= 0; +infinity when k = E.  A small margin
+ *       marks a row whose selection a small error could change.
+ *   counts_dev as in paep_predict_counted, nullable here.
+ * probs follows desc->prob as in every predict call.  With the margin the
+ * kernels keep one more candidate per row, so k <= PAEP_MAX_K still holds but
+ * the matrix-core prefill path takes k <= 15 (k <= 16 without).
+ */
+paep_status paep_predict_confidence(const paep_predict_desc *desc,
+                                    const void *x_dev, const void *W1_dev, const void *W2_dev,
+                                    const void *b1_dev, const void *b2_dev,
+                                    int32_t *idx_dev, float *probs_dev, float *logits_dev,
+                                    int32_t *counts_dev, float *margin_dev,
+                                    void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/*
+ * How paep_predict (want_margin = 0) or paep_predict_confidence with a margin
+ * output (want_margin = 1) will run this shape.  Host only; for tests and reports.
+ *   plan[0] kernel family (paep_path)
+ *   plan[1] tile configuration of the prefill family (0 otherwise):
+ *           0 128x128, 1 128x128 wide, 2 256x256, 3 256x128, 4 256x256 wide
+ *   plan[2] workgroups that share one token tile (the inner width r split
+ *           between them; 1 = no split, no workspace)
+ *   plan[3] chunks of r each of them walks
+ * Returns PAEP_OK, or the status paep_predict would give for the descriptor.
+ */
+paep_status paep_predict_plan(const paep_predict_desc *desc, int32_t want_margin, int32_t plan[4]);
+
+/*
+ * Architecture 1 of section 4.3 puts BatchNorm between the first linear layer
+ * and GELU.  At inference BatchNorm is the affine map
+ *     y_j = gamma_j (u_j - mean_j) / sqrt(var_j + eps) + beta_j
+ * on u = W1 x + b1, so it folds into the first layer:
+ *     W1'[j,:] = g_j W1[j,:],   b1'[j] = g_j (b1[j] - mean_j) + beta_j,   g_j = gamma_j / sqrt(var_j + eps)
+ * and paep_predict with act = GELU on (W1', b1') is the whole block (dropout
+ * is the identity at inference).  This call computes W1' and b1' on the
+ * device, in fp32, rounded once to the storage dtype.
+ *   W1_dev [L][r,d], b1_dev [L][r] or NULL (= 0) in `dtype`;
+ *   gamma/beta/mean/var_dev [L][r] float;  W1_out_dev [L][r,d], b1_out_dev [L][r] in `dtype`
+ *   (W1_out_dev may be W1_dev: in place).  var + eps must be > 0.
+ */
+paep_status paep_fold_batchnorm(const void *W1_dev, const void *b1_dev,
+                                const float *gamma_dev, const float *beta_dev,
+                                const float *mean_dev, const float *var_dev, float eps,
+                                int32_t L, int32_t r, int32_t d, int32_t dtype,
+                                void *W1_out_dev, void *b1_out_dev, void *stream);
+
+/* Workspace bytes for paep_group_by_expert (0 when the single-launch path
+ * serves the shape). */
 size_t paep_group_workspace_bytes(int32_t L, int32_t T, int32_t k, int32_t E);
 
 /*
@@ -161,6 +224,8 @@ size_t paep_group_workspace_bytes(int32_t L, int32_t T, int32_t k, int32_t E);
  *                     (the experts to prefetch); the rest of the row is -1
  *     n_invalid[l]    positions whose id is outside [0, E): they are skipped
  * All outputs int32.  Requires T*k < 2^31 / 2 and E <= PAEP_MAX_E.
+ * workspace_dev: at least paep_group_workspace_bytes(L, T, k, E) bytes, 16-byte
+ * aligned; may be NULL when that is 0.
  */
 paep_status paep_group_by_expert(const int32_t *idx_dev, int32_t L, int32_t T, int32_t k, int32_t E,
                                  int32_t *counts_dev, int32_t *offsets_dev, int32_t *token_pos_dev,

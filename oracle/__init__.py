@@ -194,3 +194,49 @@ def confidence_select(idx, probs, k_base: int, ratio: float):
         else:
             n_wide += 1
     return k_row, idx_out, n_wide
+
+
+def confidence_outputs(logits, idx):
+    """Confidence scores of one layer's selection (paper section 6 asks for prediction confidence scores to
+    drive dynamic over-provisioning; section 4.4 trains the predictor through a sigmoid per expert, eq. 1
+    normalises the router with a softmax).  From the scores s = logits[T,E] (float64, as returned by
+    `predict`) and the selection idx[T,k] (descending score):
+
+        softmax_topk[t,j] = exp(s[t,idx[t,j]]) / sum_{i<k} exp(s[t,idx[t,i]])     softmax over the k selected only
+        sigmoid[t,j]      = 1 / (1 + exp(-s[t,idx[t,j]]))
+        margin[t]         = (k-th largest score) - ((k+1)-th largest score), +inf when k = E
+
+    all in float64, written out as the definitions (the maximum is subtracted inside the exponentials, which
+    does not change the quotient).
+    """
+    z = np.asarray(logits, dtype=np.float64)
+    idx = np.asarray(idx, dtype=np.int64)
+    T, E = z.shape
+    k = idx.shape[1]
+    soft = np.empty((T, k), dtype=np.float64)
+    sig = np.empty((T, k), dtype=np.float64)
+    margin = np.empty(T, dtype=np.float64)
+    for t in range(T):
+        s = z[t, idx[t]]
+        w = np.exp(s - s.max())
+        soft[t] = w / w.sum()
+        sig[t] = 1.0 / (1.0 + np.exp(-s))
+        if k < E:
+            desc = np.sort(z[t])[::-1]
+            margin[t] = desc[k - 1] - desc[k]
+        else:
+            margin[t] = np.inf
+    return soft, sig, margin
+
+
+def fold_batchnorm(W1, b1, gamma, beta, mean, var, eps: float = 1e-5):
+    """BatchNorm at inference folded into the first linear layer (paper section 4.3, Architecture 1:
+    Linear -> BatchNorm -> GELU -> Dropout -> Linear; dropout is the identity at inference).  BatchNorm maps
+    u_j to gamma_j (u_j - mean_j) / sqrt(var_j + eps) + beta_j, so with g_j = gamma_j / sqrt(var_j + eps)
+        W1'[j,:] = g_j W1[j,:]        b1'[j] = g_j (b1[j] - mean_j) + beta_j
+    One layer: W1[r,d], b1[r] or None, the four statistics [r]; float64 throughout."""
+    W1 = np.asarray(W1, dtype=np.float64)
+    r = W1.shape[0]
+    b = np.zeros(r) if b1 is None else np.asarray(b1, dtype=np.float64)
+    g = np.asarray(gamma, dtype=np.float64) / np.sqrt(np.asarray(var, dtype=np.float64) + float(eps))
+    return g[:, None] * W1, g * (b - np.asarray(mean, dtype=np.float64)) + np.asarray(beta, dtype=np.float64)

@@ -22,21 +22,25 @@ F32, BF16 = 0, 1
 ACT = {"none": 0, "silu": 1, "gelu": 2}
 PATH = {"auto": 0, "simple": 1, "decode": 2, "prefill": 3}
 PATH_NAME = {v: k for k, v in PATH.items()}
+PROB = {"softmax": 0, "softmax_topk": 1, "sigmoid": 2}
+TILE_CFG = {0: "128x128", 1: "128x128 wide", 2: "256x256", 3: "256x128", 4: "256x256 wide"}
 MAX_K, MAX_E = 32, 1024
 
 STATUS_NAMES = ["PAEP_OK", "PAEP_ERR_NULL", "PAEP_ERR_SHAPE", "PAEP_ERR_K", "PAEP_ERR_DTYPE",
                 "PAEP_ERR_ALIGN", "PAEP_ERR_WORKSPACE", "PAEP_ERR_HIP", "PAEP_ERR_UNSUPPORTED"]
 
-EXPORTS = ["paep_predict_workspace_bytes", "paep_predict_resolve_path", "paep_predict", "paep_predict_counted",
+EXPORTS = ["paep_predict_workspace_bytes", "paep_predict_resolve_path", "paep_predict_plan", "paep_predict",
+           "paep_predict_counted", "paep_predict_confidence", "paep_fold_batchnorm",
            "paep_group_workspace_bytes", "paep_group_by_expert", "paep_score",
-           "paep_score_rows", "paep_confidence_select", "paep_activation_profile", "paep_probe_read", "paep_probe_mfma", "paep_status_string", "paep_version"]
+           "paep_score_rows", "paep_confidence_select", "paep_activation_profile", "paep_probe_read",
+           "paep_probe_mfma", "paep_status_string", "paep_version"]
 
 
 class PredictDesc(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int32), ("d", ctypes.c_int32), ("r", ctypes.c_int32),
                 ("E", ctypes.c_int32), ("k", ctypes.c_int32), ("L", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("act", ctypes.c_int32), ("path", ctypes.c_int32),
-                ("reserved", ctypes.c_int32),
+                ("prob", ctypes.c_int32),
                 ("x_layer_stride", ctypes.c_int64), ("w1_layer_stride", ctypes.c_int64),
                 ("w2_layer_stride", ctypes.c_int64)]
 
@@ -74,6 +78,12 @@ def lib() -> ctypes.CDLL:
         L.paep_predict.restype = ctypes.c_int
         L.paep_predict_counted.argtypes = [dp] + [vp] * 10 + [sz, vp]
         L.paep_predict_counted.restype = ctypes.c_int
+        L.paep_predict_confidence.argtypes = [dp] + [vp] * 11 + [sz, vp]
+        L.paep_predict_confidence.restype = ctypes.c_int
+        L.paep_predict_plan.argtypes = [dp, i32, ctypes.POINTER(ctypes.c_int32 * 4)]
+        L.paep_predict_plan.restype = ctypes.c_int
+        L.paep_fold_batchnorm.argtypes = [vp] * 6 + [ctypes.c_float] + [i32] * 4 + [vp] * 3
+        L.paep_fold_batchnorm.restype = ctypes.c_int
         L.paep_group_workspace_bytes.argtypes = [i32] * 4
         L.paep_group_workspace_bytes.restype = sz
         L.paep_group_by_expert.argtypes = [vp] + [i32] * 4 + [vp] * 7 + [sz, vp]
@@ -105,6 +115,14 @@ def _stream_ptr(stream) -> ctypes.c_void_p:
     if stream is None:
         stream = torch.cuda.current_stream()
     return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _on(stream):
+    """Context in which torch allocates on `stream` (its caching allocator ties a block to the stream that
+    was current when it was handed out): temporaries made for a call must belong to the stream the call's
+    kernels are enqueued on, or the allocator may hand them to someone else while those kernels still run."""
+    import contextlib
+    return contextlib.nullcontext() if stream is None else torch.cuda.stream(stream)
 
 
 def _storage_dtype(t: torch.Tensor) -> int:
@@ -143,11 +161,19 @@ class Prediction(NamedTuple):
     probs: torch.Tensor               # [L, T, k] float32
     logits: Optional[torch.Tensor]    # [L, T, E] float32 or None
     path: str
+    margin: Optional[torch.Tensor] = None   # [L, T] float32: last selected score minus the best one left out
+
+
+class Plan(NamedTuple):
+    path: str
+    tile: str                 # prefill tile configuration ("" on the other paths)
+    groups: int               # workgroups sharing one token tile (r split between them)
+    chunks_per_group: int
 
 
 def make_desc(T, d, r, E, k, L, dtype, act="none", path="auto",
-              x_layer_stride=None, w1_layer_stride=None, w2_layer_stride=None) -> PredictDesc:
-    return PredictDesc(T=T, d=d, r=r, E=E, k=k, L=L, dtype=dtype, act=ACT[act], path=PATH[path], reserved=0,
+              x_layer_stride=None, w1_layer_stride=None, w2_layer_stride=None, prob="softmax") -> PredictDesc:
+    return PredictDesc(T=T, d=d, r=r, E=E, k=k, L=L, dtype=dtype, act=ACT[act], path=PATH[path], prob=PROB[prob],
                        x_layer_stride=T * d if x_layer_stride is None else x_layer_stride,
                        w1_layer_stride=r * d if w1_layer_stride is None else w1_layer_stride,
                        w2_layer_stride=E * r if w2_layer_stride is None else w2_layer_stride)
@@ -162,11 +188,22 @@ def resolve_path(desc: PredictDesc) -> str:
     return PATH_NAME.get(p, "invalid")
 
 
+def predict_plan(desc: PredictDesc, want_margin: bool = False) -> Plan:
+    """How paep_predict will run this shape (kernel family, prefill tile configuration, r split)."""
+    out = (ctypes.c_int32 * 4)()
+    st = lib().paep_predict_plan(ctypes.byref(desc), int(bool(want_margin)), ctypes.byref(out))
+    if st != 0:
+        raise PaepError(st, "paep_predict_plan")
+    path = PATH_NAME.get(out[0], "invalid")
+    return Plan(path, TILE_CFG.get(out[1], "?") if path == "prefill" else "", int(out[2]), int(out[3]))
+
+
 def prepare_predict(x: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, k: int, *,
                     b1: Optional[torch.Tensor] = None, b2: Optional[torch.Tensor] = None,
                     act: str = "none", path: str = "auto", want_logits: bool = False,
                     out: Optional[Prediction] = None, workspace: Optional[torch.Tensor] = None,
-                    counts: Optional[torch.Tensor] = None) -> Prepared:
+                    counts: Optional[torch.Tensor] = None, prob: str = "softmax",
+                    want_margin: bool = False) -> Prepared:
     """Check and marshal one predict call; the returned object runs it (see `predict` for the arguments)."""
     if W1.dim() == 2:
         W1 = W1.unsqueeze(0)
@@ -186,7 +223,7 @@ def prepare_predict(x: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, k: int,
     for b, n in ((b1, r), (b2, E)):
         if b is not None and (b.numel() != L * n or _storage_dtype(b) != dt):
             raise ValueError("bias must be [L, r] / [L, E] in the storage dtype")
-    desc = make_desc(T, d, r, E, k, L, dt, act, path, x_layer_stride=(T * d if Lx == L and L > 1 else 0))
+    desc = make_desc(T, d, r, E, k, L, dt, act, path, x_layer_stride=(T * d if Lx == L and L > 1 else 0), prob=prob)
     if L == 1:
         desc.x_layer_stride = T * d
     dev = x.device
@@ -194,9 +231,12 @@ def prepare_predict(x: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, k: int,
         idx = torch.empty((L, T, k), dtype=torch.int32, device=dev)
         probs = torch.empty((L, T, k), dtype=torch.float32, device=dev)
         logits = torch.empty((L, T, E), dtype=torch.float32, device=dev) if want_logits else None
+        margin = torch.empty((L, T), dtype=torch.float32, device=dev) if want_margin else None
     else:
-        idx, probs, logits = out.idx, out.probs, out.logits
-        _need_device(idx, probs, logits)
+        idx, probs, logits, margin = out.idx, out.probs, out.logits, out.margin
+        _need_device(idx, probs, logits, margin)
+        if margin is not None and (tuple(margin.shape) != (L, T) or margin.dtype != torch.float32):
+            raise ValueError("margin buffer has the wrong shape or dtype")
         if tuple(idx.shape) != (L, T, k) or tuple(probs.shape) != (L, T, k) or idx.dtype != torch.int32 \
                 or probs.dtype != torch.float32:
             raise ValueError("out buffers have the wrong shape or dtype")
@@ -206,11 +246,19 @@ def prepare_predict(x: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, k: int,
     if workspace is None and need > 0:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    result = Prediction(idx, probs, logits, resolve_path(desc))
     if counts is not None:
         _need_device(counts)
         if counts.dtype != torch.int32 or tuple(counts.shape) != (L, E):
             raise ValueError("counts must be int32 [L, E]")
+    if margin is not None:
+        # the family is chosen knowing that one more candidate per row is kept
+        args = (ctypes.byref(desc), _ptr(x), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(b2),
+                _ptr(idx), _ptr(probs), _ptr(logits), _ptr(counts), _ptr(margin), _ptr(workspace), ws_bytes)
+        fam = predict_plan(desc, True).path
+        return Prepared(lib().paep_predict_confidence, "paep_predict_confidence", args,
+                        (desc, x, W1, W2, b1, b2, workspace, counts), Prediction(idx, probs, logits, fam, margin))
+    result = Prediction(idx, probs, logits, resolve_path(desc))
+    if counts is not None:
         args = (ctypes.byref(desc), _ptr(x), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(b2),
                 _ptr(idx), _ptr(probs), _ptr(logits), _ptr(counts), _ptr(workspace), ws_bytes)
         return Prepared(lib().paep_predict_counted, "paep_predict_counted", args,
@@ -224,16 +272,22 @@ def predict(x: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, k: int, *,
             b1: Optional[torch.Tensor] = None, b2: Optional[torch.Tensor] = None,
             act: str = "none", path: str = "auto", want_logits: bool = False,
             out: Optional[Prediction] = None, workspace: Optional[torch.Tensor] = None,
-            counts: Optional[torch.Tensor] = None, stream=None) -> Prediction:
+            counts: Optional[torch.Tensor] = None, prob: str = "softmax", want_margin: bool = False,
+            stream=None) -> Prediction:
     """predict(x[L|1,T,d], W1[L,r,d], W2[L,E,r], k) -> idx[L,T,k], probs[L,T,k].
 
     2-D inputs are taken as one layer.  x with a leading dimension of 1 (or
     2-D x with 3-D weights) feeds the same tokens to every layer.  `out` and
     `workspace` let a caller reuse buffers; otherwise they are allocated here.
     `counts` (int32 [L, E]) is increased by the activation counts of this call.
+    `prob` picks what probs holds ("softmax" over all E, "softmax_topk" over the k selected, "sigmoid");
+    `want_margin` adds margin[L, T], the last selected score minus the best one left out.
+    Buffers allocated here are allocated on `stream`, the stream the kernels run on.
     """
-    return prepare_predict(x, W1, W2, k, b1=b1, b2=b2, act=act, path=path, want_logits=want_logits, out=out,
-                           workspace=workspace, counts=counts)(stream)
+    with _on(stream):
+        prep = prepare_predict(x, W1, W2, k, b1=b1, b2=b2, act=act, path=path, want_logits=want_logits, out=out,
+                               workspace=workspace, counts=counts, prob=prob, want_margin=want_margin)
+    return prep(stream)
 
 
 class Grouping(NamedTuple):
@@ -268,17 +322,20 @@ def prepare_group_by_expert(idx: torch.Tensor, E: int, *, out: Optional[Grouping
     if out is None:
         out = alloc_grouping(L, T, k, E, idx.device)
     need = group_workspace_bytes(L, T, k, E)
-    if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=idx.device)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=idx.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     args = (_ptr(idx), L, T, k, E, _ptr(out.counts), _ptr(out.offsets), _ptr(out.token_pos), _ptr(out.active),
-            _ptr(out.n_active), _ptr(out.n_invalid), _ptr(workspace), workspace.numel() * workspace.element_size())
+            _ptr(out.n_active), _ptr(out.n_invalid), _ptr(workspace), ws_bytes)
     return Prepared(lib().paep_group_by_expert, "paep_group_by_expert", args, (idx, workspace), out)
 
 
 def group_by_expert(idx: torch.Tensor, E: int, *, out: Optional[Grouping] = None,
                     workspace: Optional[torch.Tensor] = None, stream=None) -> Grouping:
     """group_by_expert(idx[L,T,k]) -> counts[L,E], offsets[L,E+1], token lists, prefetch list."""
-    return prepare_group_by_expert(idx, E, out=out, workspace=workspace)(stream)
+    with _on(stream):
+        prep = prepare_group_by_expert(idx, E, out=out, workspace=workspace)
+    return prep(stream)
 
 
 def prepare_score(idx: torch.Tensor, ref_idx: torch.Tensor, E: int, *, k_row: Optional[torch.Tensor] = None,
@@ -312,7 +369,9 @@ def score(idx: torch.Tensor, ref_idx: torch.Tensor, E: int, *, k_row: Optional[t
           out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     """score(idx[L,T,k_pred], ref_idx[L,T,k_ref]) -> int64 [L,4]: n_exact, n_hit, n_cover, n_top1.
     With k_row[L,T] (int32) each row uses only its first k_row predicted ids."""
-    return prepare_score(idx, ref_idx, E, k_row=k_row, out=out)(stream)
+    with _on(stream):
+        prep = prepare_score(idx, ref_idx, E, k_row=k_row, out=out)
+    return prep(stream)
 
 
 class Widened(NamedTuple):
@@ -330,8 +389,9 @@ def confidence_select(idx: torch.Tensor, probs: torch.Tensor, k_base: int, ratio
             or not idx.is_contiguous() or not probs.is_contiguous():
         raise TypeError("idx int32 and probs float32 must be contiguous and of one shape [L, T, k_pred]")
     L, T, k_pred = idx.shape
-    out = Widened(torch.empty_like(idx), torch.empty((L, T), dtype=torch.int32, device=idx.device),
-                  torch.empty((L,), dtype=torch.int32, device=idx.device))
+    with _on(stream):
+        out = Widened(torch.empty_like(idx), torch.empty((L, T), dtype=torch.int32, device=idx.device),
+                      torch.empty((L,), dtype=torch.int32, device=idx.device))
     st = lib().paep_confidence_select(_ptr(idx), _ptr(probs), L, T, k_pred, k_base, float(ratio), _ptr(out.idx),
                                       _ptr(out.k_row), _ptr(out.n_wide), _stream_ptr(stream))
     if st != 0:
@@ -353,14 +413,41 @@ def activation_profile(counts: torch.Tensor, stream=None) -> ActivationProfile:
     if counts.dtype != torch.int32 or not counts.is_contiguous():
         raise TypeError("counts must be contiguous int32")
     L, E = counts.shape
-    out = ActivationProfile(torch.empty((L, E), dtype=torch.int32, device=counts.device),
-                            torch.empty((L,), dtype=torch.int32, device=counts.device),
-                            torch.empty((L,), dtype=torch.float64, device=counts.device))
+    with _on(stream):
+        out = ActivationProfile(torch.empty((L, E), dtype=torch.int32, device=counts.device),
+                                torch.empty((L,), dtype=torch.int32, device=counts.device),
+                                torch.empty((L,), dtype=torch.float64, device=counts.device))
     st = lib().paep_activation_profile(_ptr(counts), L, E, _ptr(out.order), _ptr(out.n_active), _ptr(out.entropy),
                                        _stream_ptr(stream))
     if st != 0:
         raise PaepError(st, "paep_activation_profile")
     return out
+
+
+def fold_batchnorm(W1: torch.Tensor, b1: Optional[torch.Tensor], gamma: torch.Tensor, beta: torch.Tensor,
+                   mean: torch.Tensor, var: torch.Tensor, eps: float = 1e-5, stream=None):
+    """BatchNorm (inference form) folded into the first linear layer: returns (W1', b1') such that
+    act(BN(W1 x + b1)) = act(W1' x + b1').  W1 [L, r, d] (or [r, d]), b1 [L, r] or None in the storage
+    dtype; gamma, beta, mean, var [L, r] float32."""
+    squeeze = W1.dim() == 2
+    if squeeze:
+        W1 = W1.unsqueeze(0)
+    L, r, d = W1.shape
+    stats = [t.reshape(L, r) for t in (gamma, beta, mean, var)]
+    _need_device(W1, b1, *stats)
+    if any(t.dtype != torch.float32 for t in stats):
+        raise TypeError("gamma, beta, mean, var must be float32")
+    dt = _storage_dtype(W1)
+    if b1 is not None and (_storage_dtype(b1) != dt or b1.numel() != L * r):
+        raise ValueError("b1 must be [L, r] in the storage dtype of W1")
+    with _on(stream):
+        W1o = torch.empty_like(W1)
+        b1o = torch.empty((L, r), dtype=W1.dtype, device=W1.device)
+    st = lib().paep_fold_batchnorm(_ptr(W1), _ptr(b1), *[_ptr(t) for t in stats], float(eps), L, r, d, dt,
+                                   _ptr(W1o), _ptr(b1o), _stream_ptr(stream))
+    if st != 0:
+        raise PaepError(st, "paep_fold_batchnorm")
+    return (W1o[0], b1o[0]) if squeeze else (W1o, b1o)
 
 
 def probe_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:

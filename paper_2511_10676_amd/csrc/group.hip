@@ -308,11 +308,18 @@ __global__ __launch_bounds__(FUSED_THREADS) void group_fused_kernel(
     for (int i = tid; i < n; i += FUSED_THREADS) dst[i] = (i < total) ? list[i] : -1;   // -1 fills the unused tail
 }
 
+// the single-launch kernel serves the layer (no workspace)
+static bool fused_fits(long long n, int E)
+{
+    const size_t lds = sizeof(int32_t) * ((size_t)FUSED_WAVES * (size_t)(E + 1) + (size_t)n);
+    return n <= FUSED_MAX_ITEMS && lds <= FUSED_MAX_LDS;
+}
+
 size_t group_workspace_bytes(int L, int T, int k, int E)
 {
     const long long n = (long long)T * k;
-    const long long nwc = wave_chunks(n) > 0 ? wave_chunks(n) : 1;
-    return sizeof(int32_t) * (size_t)L * (size_t)nwc * (size_t)(E + 1);
+    if (fused_fits(n, E)) return 0;
+    return sizeof(int32_t) * (size_t)L * (size_t)wave_chunks(n) * (size_t)(E + 1);
 }
 
 hipError_t launch_group(const int32_t* idx, int L, int T, int k, int E,
@@ -326,12 +333,10 @@ hipError_t launch_group(const int32_t* idx, int L, int T, int k, int E,
     int nbits = 0;
     while ((1 << nbits) < E) ++nbits;
     const size_t lds = sizeof(int32_t) * ((size_t)FUSED_WAVES * (size_t)(E + 1) + (size_t)n);
-    if (n <= FUSED_MAX_ITEMS && lds <= FUSED_MAX_LDS) {
-        if (lds > 48 * 1024) {
-            hipError_t err = hipFuncSetAttribute((const void*)group_fused_kernel,
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (err != hipSuccess) return err;
-        }
+    if (fused_fits(n, E)) {
+        static LdsLimit limit;
+        hipError_t err = ensure_lds_limit(limit, (const void*)group_fused_kernel, lds);
+        if (err != hipSuccess) return err;
         hipLaunchKernelGGL(group_fused_kernel, dim3(L), dim3(FUSED_THREADS), lds, stream, idx, n, E, nbits, counts,
                            offsets, token_pos, active, n_active, n_invalid);
         return hipGetLastError();

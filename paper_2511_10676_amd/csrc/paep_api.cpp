@@ -12,7 +12,8 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 paep_status check_desc(const paep_predict_desc* d)
 {
     if (!d) return PAEP_ERR_NULL;
-    if (d->reserved != 0) return PAEP_ERR_SHAPE;
+    if (d->prob != PAEP_PROB_SOFTMAX_ALL && d->prob != PAEP_PROB_SOFTMAX_TOPK && d->prob != PAEP_PROB_SIGMOID)
+        return PAEP_ERR_DTYPE;
     if (d->dtype != PAEP_F32 && d->dtype != PAEP_BF16) return PAEP_ERR_DTYPE;
     if (d->act != PAEP_ACT_NONE && d->act != PAEP_ACT_SILU && d->act != PAEP_ACT_GELU) return PAEP_ERR_DTYPE;
     if (d->path < PAEP_PATH_AUTO || d->path > PAEP_PATH_PREFILL) return PAEP_ERR_UNSUPPORTED;
@@ -33,7 +34,7 @@ paep::PredictArgs to_args(const paep_predict_desc* d)
 {
     paep::PredictArgs a{};
     a.T = d->T; a.d = d->d; a.r = d->r; a.E = d->E; a.k = d->k; a.L = d->L;
-    a.dtype = d->dtype; a.act = d->act;
+    a.dtype = d->dtype; a.act = d->act; a.prob_mode = d->prob;
     a.x_stride = d->x_layer_stride; a.w1_stride = d->w1_layer_stride; a.w2_stride = d->w2_layer_stride;
     return a;
 }
@@ -99,6 +100,7 @@ static paep_status predict_common(const paep_predict_desc* desc,
                                   const void* x_dev, const void* W1_dev, const void* W2_dev,
                                   const void* b1_dev, const void* b2_dev,
                                   int32_t* idx_dev, float* probs_dev, float* logits_dev, int32_t* counts_dev,
+                                  float* margin_dev,
                                   void* workspace_dev, size_t workspace_bytes, void* stream)
 {
     const paep_status st = check_desc(desc);
@@ -107,6 +109,7 @@ static paep_status predict_common(const paep_predict_desc* desc,
     if (desc->T > 0 && (!x_dev || !idx_dev || !probs_dev)) return PAEP_ERR_NULL;
     if (!aligned16(x_dev) || !aligned16(W1_dev) || !aligned16(W2_dev)) return PAEP_ERR_ALIGN;
     paep::PredictArgs a = to_args(desc);
+    a.margin = margin_dev;                                   // the families differ in how many candidates they can keep
     const int path = resolve(desc, a);
     if (!path) return PAEP_ERR_UNSUPPORTED;
     const size_t need = (path == PAEP_PATH_DECODE) ? paep::decode_workspace_bytes(a)
@@ -134,7 +137,7 @@ paep_status paep_predict(const paep_predict_desc* desc,
                          void* workspace_dev, size_t workspace_bytes, void* stream)
 {
     return predict_common(desc, x_dev, W1_dev, W2_dev, b1_dev, b2_dev, idx_dev, probs_dev, logits_dev, nullptr,
-                          workspace_dev, workspace_bytes, stream);
+                          nullptr, workspace_dev, workspace_bytes, stream);
 }
 
 paep_status paep_predict_counted(const paep_predict_desc* desc,
@@ -145,7 +148,55 @@ paep_status paep_predict_counted(const paep_predict_desc* desc,
 {
     if (!counts_dev) return PAEP_ERR_NULL;
     return predict_common(desc, x_dev, W1_dev, W2_dev, b1_dev, b2_dev, idx_dev, probs_dev, logits_dev, counts_dev,
-                          workspace_dev, workspace_bytes, stream);
+                          nullptr, workspace_dev, workspace_bytes, stream);
+}
+
+paep_status paep_predict_confidence(const paep_predict_desc* desc,
+                                    const void* x_dev, const void* W1_dev, const void* W2_dev,
+                                    const void* b1_dev, const void* b2_dev,
+                                    int32_t* idx_dev, float* probs_dev, float* logits_dev,
+                                    int32_t* counts_dev, float* margin_dev,
+                                    void* workspace_dev, size_t workspace_bytes, void* stream)
+{
+    return predict_common(desc, x_dev, W1_dev, W2_dev, b1_dev, b2_dev, idx_dev, probs_dev, logits_dev, counts_dev,
+                          margin_dev, workspace_dev, workspace_bytes, stream);
+}
+
+paep_status paep_predict_plan(const paep_predict_desc* desc, int32_t want_margin, int32_t plan[4])
+{
+    const paep_status st = check_desc(desc);
+    if (st != PAEP_OK) return st;
+    if (!plan) return PAEP_ERR_NULL;
+    paep::PredictArgs a = to_args(desc);
+    static float margin_wanted;                              // only its address matters: "a margin output is present"
+    a.margin = want_margin ? &margin_wanted : nullptr;
+    const int path = resolve(desc, a);
+    if (!path) return PAEP_ERR_UNSUPPORTED;
+    plan[0] = path; plan[1] = 0; plan[2] = 1; plan[3] = 0;
+    if (path == PAEP_PATH_PREFILL) {
+        if (a.T == 0) a.T = 1;
+        int cfg = 0, groups = 1, cpg = 0;
+        paep::prefill_plan(a, &cfg, &groups, &cpg);
+        plan[1] = cfg; plan[2] = groups; plan[3] = cpg;
+    }
+    return PAEP_OK;
+}
+
+paep_status paep_fold_batchnorm(const void* W1_dev, const void* b1_dev, const float* gamma_dev,
+                                const float* beta_dev, const float* mean_dev, const float* var_dev, float eps,
+                                int32_t L, int32_t r, int32_t d, int32_t dtype, void* W1_out_dev,
+                                void* b1_out_dev, void* stream)
+{
+    if (L < 1 || r < 1 || d < 1 || (long long)L * r >= (1ll << 31) || (long long)L * r * d >= (1ll << 40))
+        return PAEP_ERR_SHAPE;
+    if (dtype != PAEP_F32 && dtype != PAEP_BF16) return PAEP_ERR_DTYPE;
+    if (!(eps >= 0.0f)) return PAEP_ERR_SHAPE;               // also rejects NaN
+    if (!W1_dev || !gamma_dev || !beta_dev || !mean_dev || !var_dev || !W1_out_dev || !b1_out_dev)
+        return PAEP_ERR_NULL;
+    const hipError_t err = paep::launch_fold_batchnorm(W1_dev, b1_dev, gamma_dev, beta_dev, mean_dev, var_dev, eps,
+                                                       L, r, d, dtype, W1_out_dev, b1_out_dev,
+                                                       static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? PAEP_OK : PAEP_ERR_HIP;
 }
 
 static paep_status check_group(int32_t L, int32_t T, int32_t k, int32_t E)
@@ -172,7 +223,7 @@ paep_status paep_group_by_expert(const int32_t* idx_dev, int32_t L, int32_t T, i
     if (!counts_dev || !offsets_dev || !active_dev || !n_active_dev || !n_invalid_dev) return PAEP_ERR_NULL;
     if (T > 0 && (!idx_dev || !token_pos_dev)) return PAEP_ERR_NULL;
     const size_t need = paep::group_workspace_bytes(L, T, k, E);
-    if (!workspace_dev || !aligned16(workspace_dev) || workspace_bytes < need) return PAEP_ERR_WORKSPACE;
+    if (need > 0 && (!workspace_dev || !aligned16(workspace_dev) || workspace_bytes < need)) return PAEP_ERR_WORKSPACE;
     const hipError_t err = paep::launch_group(idx_dev, L, T, k, E, counts_dev, offsets_dev, token_pos_dev,
                                               active_dev, n_active_dev, n_invalid_dev, workspace_dev,
                                               static_cast<hipStream_t>(stream));

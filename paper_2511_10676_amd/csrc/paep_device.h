@@ -6,9 +6,14 @@
 //    lower expert id" (the tie rule of the C header),
 //  * a sorted top-K list kept in registers, filled by streaming over a row of
 //    scores and merged across the lanes that share a row with wave shuffles,
-//  * the softmax (eq. 1 of the paper) gathered at the selected experts,
-//  * optionally, one integer atomic per selection into the layer's activation
-//    counts (the histogram that grouping would compute, fused into the epilogue).
+//  * the softmax (eq. 1 of the paper) gathered at the selected experts, or one
+//    of the other two confidence scores (softmax over the selected experts
+//    only; sigmoid, the function the predictor is trained through, section 4.4),
+//  * optionally, the margin between the last selected score and the best one
+//    left out (the confidence signal of the paper's closing section),
+//  * optionally, one integer atomic per selection into activation counters
+//    (the histogram that grouping would compute, fused into the epilogue); the
+//    counters may live in LDS (one flush per workgroup) or in global memory.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -96,14 +101,30 @@ struct TopList {
     }
 };
 
+// What the epilogue writes besides idx.
+//   prob_mode 0: probs[j] = softmax over all E scores, gathered at the selection (eq. 1)
+//             1: probs[j] = softmax over the k selected scores only
+//             2: probs[j] = sigmoid of the selected score
+//   margin:   nullable; margin[row] = score of the last selected expert minus the best
+//             score left out (+inf when k = E)
+//   counts:   nullable; counts[e] += 1 per selection of expert e (LDS or global)
+struct EpilogueOut {
+    int prob_mode;
+    float* margin_row;
+    int32_t* counts_row;
+};
+
+__device__ __forceinline__ float sigmoidf_(float v) { return 1.0f / (1.0f + __expf(-v)); }
+
 // Softmax + top-k of one row of E scores held in LDS, computed by G
 // consecutive lanes (G a power of two, the group aligned to G).  Lane g of
 // the group scans e = g, g+G, ...; the per-lane lists are merged with
 // xor-shuffles so that every lane ends with the row's list; lane g writes
-// outputs j = g, g+G, ... < k.
+// outputs j = g, g+G, ... < k.  KMAX >= k, and >= k + 1 when the margin is
+// wanted and k < E.
 template <int KMAX, int G>
 __device__ __forceinline__ void row_softmax_topk(const float* zrow, int E, int k, int g,
-                                                 int32_t* idx_row, float* probs_row, int32_t* counts_row)
+                                                 int32_t* idx_row, float* probs_row, const EpilogueOut& o)
 {
     TopList<KMAX> top;
     top.clear();
@@ -118,42 +139,58 @@ __device__ __forceinline__ void row_softmax_topk(const float* zrow, int E, int k
     }
     const float m = key_score(top.key[0]);       // row maximum (NaNs order last)
     float s = 0.0f;
-    for (int e = g; e < E; e += G) {
-        const float v = zrow[e];
-        if (v == v) s += __expf(v - m);
-    }
+    if (o.prob_mode == 0) {
+        for (int e = g; e < E; e += G) {
+            const float v = zrow[e];
+            if (v == v) s += __expf(v - m);
+        }
 #pragma unroll
-    for (int mask = 1; mask < G; mask <<= 1) s += __shfl_xor(s, mask, 64);
+        for (int mask = 1; mask < G; mask <<= 1) s += __shfl_xor(s, mask, 64);
+    } else if (o.prob_mode == 1) {
+#pragma unroll
+        for (int j = 0; j < KMAX; ++j)           // every lane holds the whole list: same sum, same order
+            if (j < k) s += __expf(key_score(top.key[j]) - m);
+    }
     const float inv = 1.0f / s;
 #pragma unroll
     for (int j = 0; j < KMAX; ++j) {
         if (j < k && (j % G) == g) {
+            const float sc = key_score(top.key[j]);
             idx_row[j] = key_expert(top.key[j]);
-            probs_row[j] = __expf(key_score(top.key[j]) - m) * inv;
-            if (counts_row) atomicAdd(&counts_row[key_expert(top.key[j])], 1);   // activation counts (exact: integers)
+            probs_row[j] = (o.prob_mode == 2) ? sigmoidf_(sc) : __expf(sc - m) * inv;
+            if (o.counts_row) atomicAdd(&o.counts_row[key_expert(top.key[j])], 1);   // activation counts (exact: integers)
         }
+    }
+    if (o.margin_row && g == 0) {
+        float mg = __builtin_inff();
+#pragma unroll
+        for (int j = 1; j < KMAX; ++j)
+            if (j == k && k < E) mg = key_score(top.key[j - 1]) - key_score(top.key[j]);
+        *o.margin_row = mg;
     }
 }
 
-// Dispatch on the smallest list length that holds k.
+// Dispatch on the smallest list length that holds k (and the runner-up, when the margin is wanted).
 template <int G>
 __device__ __forceinline__ void row_softmax_topk_any(const float* zrow, int E, int k, int g,
-                                                     int32_t* idx_row, float* probs_row, int32_t* counts_row)
+                                                     int32_t* idx_row, float* probs_row, const EpilogueOut& o)
 {
-    if (k <= 2)       row_softmax_topk<2, G>(zrow, E, k, g, idx_row, probs_row, counts_row);
-    else if (k <= 8)  row_softmax_topk<8, G>(zrow, E, k, g, idx_row, probs_row, counts_row);
-    else if (k <= 16) row_softmax_topk<16, G>(zrow, E, k, g, idx_row, probs_row, counts_row);
-    else              row_softmax_topk<32, G>(zrow, E, k, g, idx_row, probs_row, counts_row);
+    const int need = k + ((o.margin_row && k < E) ? 1 : 0);
+    if (need <= 2)       row_softmax_topk<2, G>(zrow, E, k, g, idx_row, probs_row, o);
+    else if (need <= 8)  row_softmax_topk<8, G>(zrow, E, k, g, idx_row, probs_row, o);
+    else if (need <= 16) row_softmax_topk<16, G>(zrow, E, k, g, idx_row, probs_row, o);
+    else                 row_softmax_topk<33, G>(zrow, E, k, g, idx_row, probs_row, o);
 }
 
 // Softmax + top-k of one row held in registers by a whole wave: lane l owns
-// z[v] = score of expert l + 64*v (v < NV).  k rounds of "wave-wide maximum
-// of the keys still in play"; the lane that owns the winner retires it.  Lane
-// j keeps the j-th winner and writes output j.  All reductions are xor
-// butterflies, so the result does not depend on scheduling.
+// z[v] = score of expert l + 64*v (v < NV).  k rounds (one more when the margin
+// is wanted) of "wave-wide maximum of the keys still in play"; the lane that
+// owns the winner retires it.  Lane j keeps the j-th winner and writes output
+// j.  All reductions are xor butterflies, so the result does not depend on
+// scheduling.
 template <int NV>
 __device__ __forceinline__ void wave_softmax_topk(const float (&z)[NV], int E, int k, int lane,
-                                                  int32_t* idx_row, float* probs_row, int32_t* counts_row)
+                                                  int32_t* idx_row, float* probs_row, const EpilogueOut& o)
 {
     uint64_t key[NV];
 #pragma unroll
@@ -162,43 +199,58 @@ __device__ __forceinline__ void wave_softmax_topk(const float (&z)[NV], int E, i
         key[v] = (e < E) ? make_key(z[v], e) : 0ull;
     }
     uint64_t mine = 0ull;
-    for (int j = 0; j < k; ++j) {
+    const int rounds = k + ((o.margin_row && k < E) ? 1 : 0);
+    for (int j = 0; j < rounds; ++j) {
         uint64_t best = key[0];
 #pragma unroll
         for (int v = 1; v < NV; ++v) best = key[v] > best ? key[v] : best;
 #pragma unroll
         for (int mask = 1; mask < 64; mask <<= 1) {
-            const uint64_t o = __shfl_xor((unsigned long long)best, mask, 64);
-            best = o > best ? o : best;
+            const uint64_t ot = __shfl_xor((unsigned long long)best, mask, 64);
+            best = ot > best ? ot : best;
         }
 #pragma unroll
         for (int v = 0; v < NV; ++v) key[v] = (key[v] == best) ? 0ull : key[v];
         if (lane == j) mine = best;
     }
     const float m = key_score(__shfl((unsigned long long)mine, 0, 64));     // row maximum
+    const float sc = key_score(mine);
     float s = 0.0f;
+    if (o.prob_mode == 0) {
 #pragma unroll
-    for (int v = 0; v < NV; ++v) {
-        const int e = lane + 64 * v;
-        if (e < E && z[v] == z[v]) s += __expf(z[v] - m);
+        for (int v = 0; v < NV; ++v) {
+            const int e = lane + 64 * v;
+            if (e < E && z[v] == z[v]) s += __expf(z[v] - m);
+        }
+    } else if (o.prob_mode == 1) {
+        if (lane < k) s = __expf(sc - m);
     }
+    if (o.prob_mode != 2) {
 #pragma unroll
-    for (int mask = 1; mask < 64; mask <<= 1) s += __shfl_xor(s, mask, 64);
+        for (int mask = 1; mask < 64; mask <<= 1) s += __shfl_xor(s, mask, 64);
+    }
+    if (o.margin_row) {
+        const float last = key_score(__shfl((unsigned long long)mine, k - 1, 64));
+        const float next = key_score(__shfl((unsigned long long)mine, k < 64 ? k : 63, 64));
+        if (lane == 0) *o.margin_row = (k < E) ? last - next : __builtin_inff();
+    }
     if (lane < k) {
         idx_row[lane] = key_expert(mine);
-        probs_row[lane] = __expf(key_score(mine) - m) / s;
-        if (counts_row) atomicAdd(&counts_row[key_expert(mine)], 1);
+        probs_row[lane] = (o.prob_mode == 2) ? sigmoidf_(sc) : __expf(sc - m) / s;
+        if (o.counts_row) atomicAdd(&o.counts_row[key_expert(mine)], 1);
     }
 }
 
-// Same, for kernels that only accept k <= 16 (keeps their register budget small).
+// Same, for kernels that only accept lists of up to 16 (keeps their register budget small):
+// k <= 16, and k <= 15 when the margin is wanted and k < E.
 template <int G>
 __device__ __forceinline__ void row_softmax_topk_upto16(const float* zrow, int E, int k, int g,
-                                                        int32_t* idx_row, float* probs_row, int32_t* counts_row)
+                                                        int32_t* idx_row, float* probs_row, const EpilogueOut& o)
 {
-    if (k <= 2)      row_softmax_topk<2, G>(zrow, E, k, g, idx_row, probs_row, counts_row);
-    else if (k <= 8) row_softmax_topk<8, G>(zrow, E, k, g, idx_row, probs_row, counts_row);
-    else             row_softmax_topk<16, G>(zrow, E, k, g, idx_row, probs_row, counts_row);
+    const int need = k + ((o.margin_row && k < E) ? 1 : 0);
+    if (need <= 2)      row_softmax_topk<2, G>(zrow, E, k, g, idx_row, probs_row, o);
+    else if (need <= 8) row_softmax_topk<8, G>(zrow, E, k, g, idx_row, probs_row, o);
+    else                row_softmax_topk<16, G>(zrow, E, k, g, idx_row, probs_row, o);
 }
 
 }  // namespace paep

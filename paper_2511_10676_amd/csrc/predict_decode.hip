@@ -200,7 +200,7 @@ static constexpr int FIN_NV = 8;                          // experts per lane: E
 __global__ __launch_bounds__(DEC_THREADS) void decode_finalize_kernel(
     int T, int E, int k, int S, int rows_total, const float* __restrict__ partial,
     const uint16_t* __restrict__ b2, int32_t* __restrict__ idx, float* __restrict__ probs,
-    float* __restrict__ logits, int32_t* __restrict__ counts)
+    float* __restrict__ logits, int32_t* __restrict__ counts, int prob_mode, float* __restrict__ margin)
 {
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * (DEC_THREADS / 64) + (threadIdx.x >> 6);
@@ -235,8 +235,8 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_finalize_kernel(
         }
         z[v] = acc;
     }
-    wave_softmax_topk<FIN_NV>(z, E, k, lane, idx + (long long)row * k, probs + (long long)row * k,
-                              counts ? counts + (long long)layer * E : nullptr);
+    const EpilogueOut eo{prob_mode, margin ? margin + row : nullptr, counts ? counts + (long long)layer * E : nullptr};
+    wave_softmax_topk<FIN_NV>(z, E, k, lane, idx + (long long)row * k, probs + (long long)row * k, eo);
 }
 
 bool decode_supported(const PredictArgs& a)
@@ -277,7 +277,7 @@ hipError_t launch_predict_decode(const PredictArgs& a)
     const int rows_per_wg = DEC_THREADS / 64;
     hipLaunchKernelGGL(decode_finalize_kernel, dim3((rows + rows_per_wg - 1) / rows_per_wg), dim3(DEC_THREADS), 0,
                        a.stream, a.T, a.E, a.k, S, rows, partial, (const uint16_t*)a.b2, a.idx, a.probs, a.logits,
-                       a.counts);
+                       a.counts, a.prob_mode, a.margin);
     return hipGetLastError();
 }
 

@@ -85,7 +85,8 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ W1, const uint16_t* __restrict__ W2,
     const uint16_t* __restrict__ b1, const uint16_t* __restrict__ b2,
     int32_t* __restrict__ idx, float* __restrict__ probs, float* __restrict__ logits,
-    float* __restrict__ zpart, int* __restrict__ tickets, int32_t* __restrict__ counts)
+    float* __restrict__ zpart, int* __restrict__ tickets, int32_t* __restrict__ counts,
+    int prob_mode, float* __restrict__ margin)
 {
     constexpr int BM = C::BM, BN = C::BN, BK = C::BK, NS = C::NS, WR = C::WR, WT = C::WT;
     constexpr int WM = C::WM, WN = C::WN, MI = C::MI, NI = C::NI, CPR = C::CPR, RPI = C::RPI;
@@ -415,6 +416,20 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     }
     __syncthreads();                                       // all tile reads done before LDS is reused
 
+    // Activation counters of this workgroup's rows, kept in LDS behind the score
+    // tile and flushed to the layer's counts once at the end: at most E global
+    // atomics per workgroup instead of one per selection.
+    int32_t* cnt_lds = (int32_t*)(smem_raw + sizeof(float) * (size_t)PfZRows<C, EB32>::value * (size_t)(E + 1));
+    if (counts)
+        for (int e = tid; e < E; e += C::THREADS) cnt_lds[e] = 0;
+    auto flush_counts = [&]() {                              // after a barrier that follows the last row's epilogue
+        if (counts)
+            for (int e = tid; e < E; e += C::THREADS) {
+                const int c = cnt_lds[e];
+                if (c) atomicAdd(&counts[(long long)layer * E + e], c);
+            }
+    };
+
     // acc2[eb][ni][i] = partial score of token wt*WN + ni*32 + l32,
     //                   expert eb*32 + 8*(i/4) + 4*g + i%4, over this wave's hidden units.
     // The score tile goes to LDS ZROWS tokens at a time (all of it unless E is
@@ -466,8 +481,8 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
         // the lanes of a group take the same branch (same token)
         if (tbase + tl < T) {
             const long long row = (long long)layer * T + tbase + tl;
-            row_softmax_topk_upto16<ZG>(zs + tl * ZP, E, k, gg, idx + row * k, probs + row * k,
-                                        counts ? counts + (long long)layer * E : nullptr);
+            const EpilogueOut eo{prob_mode, margin ? margin + row : nullptr, counts ? cnt_lds : nullptr};
+            row_softmax_topk_upto16<ZG>(zs + tl * ZP, E, k, gg, idx + row * k, probs + row * k, eo);
         }
         __syncthreads();
     };
@@ -478,6 +493,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
             regs_to_lds(zp);
             finish_rows(zp);
         }
+        flush_counts();
         return;
     }
 
@@ -533,6 +549,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
         __syncthreads();
         finish_rows(zp);
     }
+    flush_counts();
 }
 
 __global__ void prefill_clear_tickets(int* tickets, int n)
@@ -567,14 +584,16 @@ typedef PfCfg<128, 128, 32, 4, 1, 4, 1> CfgSmallWide;
 template <class C, int EB32>
 static size_t cfg_lds_bytes(int E)
 {
-    const size_t z = sizeof(float) * (size_t)PfZRows<C, EB32>::value * (size_t)(E + 1);
+    // score tile of the epilogue, then E activation counters
+    const size_t z = sizeof(float) * (size_t)PfZRows<C, EB32>::value * (size_t)(E + 1) + sizeof(int32_t) * (size_t)E;
     return z > (size_t)C::TILE_BYTES ? z : (size_t)C::TILE_BYTES;
 }
 
 bool prefill_supported(const PredictArgs& a)
 {
     // the copy offsets are 32-bit byte offsets into one layer's W1 and x
-    return a.dtype == 1 && a.T >= 1 && a.d % 32 == 0 && a.r % 128 == 0 && a.E <= 256 && a.k <= 16 &&
+    const int list = a.k + ((a.margin && a.k < a.E) ? 1 : 0);     // the epilogue keeps sorted lists of up to 16
+    return a.dtype == 1 && a.T >= 1 && a.d % 32 == 0 && a.r % 128 == 0 && a.E <= 256 && list <= 16 &&
            (long long)a.r * a.d * 2 < (1ll << 31) && ((long long)a.T + 256) * a.d * 2 < (1ll << 31);
 }
 
@@ -630,12 +649,14 @@ static hipError_t launch_cfg(const PredictArgs& a)
         hipLaunchKernelGGL(prefill_clear_tickets, dim3((nt + 255) / 256), dim3(256), 0, a.stream, tickets, nt);
     }
     auto kern = prefill_kernel<C, EB32>;
-    hipError_t err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static LdsLimit limit;
+    hipError_t err = ensure_lds_limit(limit, (const void*)kern, lds);
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(kern, dim3(total), dim3(C::THREADS), lds, a.stream, a.T, a.d, a.r, a.E, a.k, a.act, tiles,
                        total, groups, cpg, a.x_stride, a.w1_stride, a.w2_stride, (const uint16_t*)a.x,
                        (const uint16_t*)a.W1, (const uint16_t*)a.W2, (const uint16_t*)a.b1,
-                       (const uint16_t*)a.b2, a.idx, a.probs, a.logits, zpart, tickets, a.counts);
+                       (const uint16_t*)a.b2, a.idx, a.probs, a.logits, zpart, tickets, a.counts, a.prob_mode,
+                       a.margin);
     return hipGetLastError();
 }
 
@@ -650,6 +671,25 @@ static int pick_cfg(const PredictArgs& a)
     if (a.E <= 64) return (large && a.r % 256 == 0) ? 2 : 0;
     if (!(large && a.d % 64 == 0)) return 1;                  // the configurations below walk d in steps of 64
     return (a.E <= 128 && a.r % 256 == 0) ? 4 : 3;
+}
+
+template <class C>
+static void cfg_plan(const PredictArgs& a, int* groups, int* cpg)
+{
+    *groups = prefill_groups<C>(a);
+    *cpg = a.r / C::BN / *groups;
+}
+
+void prefill_plan(const PredictArgs& a, int* cfg, int* groups, int* chunks_per_group)
+{
+    *cfg = pick_cfg(a);
+    switch (*cfg) {
+    case 2: cfg_plan<CfgBig>(a, groups, chunks_per_group); break;
+    case 3: cfg_plan<CfgMid>(a, groups, chunks_per_group); break;
+    case 4: cfg_plan<CfgBigWide>(a, groups, chunks_per_group); break;
+    case 1: cfg_plan<CfgSmallWide>(a, groups, chunks_per_group); break;
+    default: cfg_plan<CfgSmall>(a, groups, chunks_per_group); break;
+    }
 }
 
 size_t prefill_workspace_bytes(const PredictArgs& a)

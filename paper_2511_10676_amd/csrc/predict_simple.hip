@@ -28,7 +28,8 @@ __global__ __launch_bounds__(SIMPLE_THREADS) void predict_simple_kernel(
     int Tn, int d, int r, int E, int k, int act, long long xs, long long w1s, long long w2s,
     const T* __restrict__ x, const T* __restrict__ W1, const T* __restrict__ W2,
     const T* __restrict__ b1, const T* __restrict__ b2,
-    int32_t* __restrict__ idx, float* __restrict__ probs, float* __restrict__ logits, int32_t* __restrict__ counts)
+    int32_t* __restrict__ idx, float* __restrict__ probs, float* __restrict__ logits, int32_t* __restrict__ counts,
+    int prob_mode, float* __restrict__ margin)
 {
     extern __shared__ float smem[];
     float* xt = smem;                    // [TS][d]
@@ -98,8 +99,9 @@ __global__ __launch_bounds__(SIMPLE_THREADS) void predict_simple_kernel(
     const int t = t0 + wave;
     if (t < Tn) {
         const long long row = (long long)layer * Tn + t;
-        row_softmax_topk_any<64>(zt + wave * E, E, k, lane, idx + row * k, probs + row * k,
-                                 counts ? counts + (long long)layer * E : nullptr);
+        const EpilogueOut eo{prob_mode, margin ? margin + row : nullptr,
+                             counts ? counts + (long long)layer * E : nullptr};
+        row_softmax_topk_any<64>(zt + wave * E, E, k, lane, idx + row * k, probs + row * k, eo);
     }
 }
 
@@ -116,13 +118,13 @@ hipError_t launch_predict_simple(const PredictArgs& a)
 #define PAEP_LAUNCH_SIMPLE(TY, RH)                                                                   \
     do {                                                                                             \
         auto kern = predict_simple_kernel<TY, RH>;                                                   \
-        err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,     \
-                                  (int)lds);                                                         \
+        static LdsLimit limit;                                                                       \
+        err = ensure_lds_limit(limit, (const void*)kern, lds);                                       \
         if (err != hipSuccess) return err;                                                           \
         hipLaunchKernelGGL(kern, grid, dim3(SIMPLE_THREADS), lds, a.stream, a.T, a.d, a.r, a.E, a.k, \
                            a.act, a.x_stride, a.w1_stride, a.w2_stride, (const TY*)a.x,              \
                            (const TY*)a.W1, (const TY*)a.W2, (const TY*)a.b1, (const TY*)a.b2,       \
-                           a.idx, a.probs, a.logits, a.counts);                                                \
+                           a.idx, a.probs, a.logits, a.counts, a.prob_mode, a.margin);               \
     } while (0)
     if (a.dtype == 0) PAEP_LAUNCH_SIMPLE(float, false);
     else              PAEP_LAUNCH_SIMPLE(uint16_t, true);

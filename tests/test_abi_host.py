@@ -48,9 +48,9 @@ def test_predict_rejects_bad_descriptors():
     bad_path = _desc()
     bad_path.path = 9
     assert _predict(bad_path) == E_UNSUP
-    res = _desc()
-    res.reserved = 1
-    assert _predict(res) == E_SHAPE
+    bad_prob = _desc()
+    bad_prob.prob = 3
+    assert _predict(bad_prob) == E_DTYPE
     for kw in (dict(T=-1), dict(L=0), dict(d=260), dict(d=0), dict(r=12), dict(E=0), dict(E=1025)):
         assert _predict(_desc(**kw)) == E_SHAPE, kw
     for kw in (dict(k=0), dict(k=17), dict(E=64, k=33)):
@@ -116,10 +116,16 @@ def test_group_rejects_bad_arguments():
     assert _group(T=1 << 29, k=2) == E_SHAPE
     assert _group(outs=(None,) + (FAKE,) * 5) == E_NULL
     assert _group(T=4, idx=None) == E_NULL
-    assert _group(T=4, ws=None) == E_WS
-    assert _group(T=4096, k=8, E=256, ws_bytes=16) == E_WS
-    assert B.group_workspace_bytes(1, 4096, 8, 256) == 4 * 32 * 257
-    assert B.group_workspace_bytes(3, 0, 8, 256) == 4 * 3 * 257
+    # more than 32768 selections per layer: three launches that meet in a workspace
+    assert _group(T=8192, k=8, E=256, ws=None) == E_WS
+    assert _group(T=8192, k=8, E=256, ws_bytes=16) == E_WS
+    assert _group(T=8192, k=8, E=256, ws=ODD) == E_WS
+    assert B.group_workspace_bytes(1, 8192, 8, 256) == 4 * 64 * 257
+    assert B.group_workspace_bytes(3, 8192, 8, 256) == 3 * 4 * 64 * 257
+    # shorter layers run in one launch out of LDS and need none (a NULL workspace is then accepted:
+    # checked with real buffers in the GPU tests, since every valid call launches)
+    assert B.group_workspace_bytes(1, 4096, 8, 256) == 0
+    assert B.group_workspace_bytes(3, 0, 8, 256) == 0
     assert B.group_workspace_bytes(0, 1, 1, 1) == 0
 
 
@@ -165,3 +171,37 @@ def test_counted_predict_needs_its_counts():
     f = B.lib().paep_predict_counted
     assert f(ctypes.byref(d), FAKE, FAKE, FAKE, None, None, FAKE, FAKE, None, None, FAKE, 1 << 30, None) == E_NULL
     assert f(ctypes.byref(_desc(T=4, k=0)), FAKE, FAKE, FAKE, None, None, FAKE, FAKE, None, FAKE, FAKE, 1 << 30, None) == E_K
+
+
+def test_plan_reports_the_family_and_the_tile_choice():
+    # DeepSeek-V2-Lite-shaped prefill: 256 x 256 tiles, every workgroup walks all eight chunks of r
+    p = B.predict_plan(B.make_desc(4096, 2048, 2048, 64, 6, 26, B.BF16))
+    assert p == B.Plan("prefill", "256x256", 1, 8)
+    # a single layer of the same: too few tiles, r is split over workgroups that meet in the workspace
+    p1 = B.predict_plan(B.make_desc(4096, 2048, 2048, 64, 6, 1, B.BF16))
+    assert p1.path == "prefill" and p1.groups > 1 and p1.groups * p1.chunks_per_group * 128 in (2048, 4096)
+    assert B.predict_plan(B.make_desc(8, 2048, 2048, 64, 6, 26, B.BF16)).path == "decode"
+    assert B.predict_plan(B.make_desc(512, 256, 64, 16, 2, 1, B.F32)) == B.Plan("simple", "", 1, 0)
+    # a margin output makes the matrix-core family keep one more candidate: k = 16 no longer fits there
+    d16 = B.make_desc(4096, 2048, 2048, 64, 16, 26, B.BF16)
+    assert B.predict_plan(d16).path == "prefill" and B.predict_plan(d16, want_margin=True).path == "simple"
+    bad = B.make_desc(4096, 2048, 2048, 64, 0, 26, B.BF16)
+    out = (ctypes.c_int32 * 4)()
+    assert B.lib().paep_predict_plan(ctypes.byref(bad), 0, ctypes.byref(out)) == E_K
+    assert B.lib().paep_predict_plan(ctypes.byref(d16), 0, None) == E_NULL
+
+
+def test_confidence_predict_and_fold_reject_bad_arguments():
+    f = B.lib().paep_predict_confidence
+    d = _desc(T=4)
+    assert f(ctypes.byref(d), None, FAKE, FAKE, None, None, FAKE, FAKE, None, None, FAKE, None, 0, None) == E_NULL
+    assert f(ctypes.byref(_desc(T=4, k=40, E=64)), FAKE, FAKE, FAKE, None, None, FAKE, FAKE, None, None, FAKE, None, 0, None) == E_K
+    pf = B.make_desc(4096, 2048, 2048, 64, 16, 26, B.BF16, path="prefill")
+    assert f(ctypes.byref(pf), FAKE, FAKE, FAKE, None, None, FAKE, FAKE, None, None, FAKE, None, 0, None) == E_UNSUP
+    g = B.lib().paep_fold_batchnorm
+    eps = ctypes.c_float(1e-5)
+    assert g(FAKE, None, FAKE, FAKE, FAKE, FAKE, eps, 0, 8, 8, B.F32, FAKE, FAKE, None) == E_SHAPE
+    assert g(FAKE, None, FAKE, FAKE, FAKE, FAKE, eps, 1, 8, 8, 5, FAKE, FAKE, None) == E_DTYPE
+    assert g(FAKE, None, FAKE, FAKE, FAKE, FAKE, ctypes.c_float(-1.0), 1, 8, 8, B.F32, FAKE, FAKE, None) == E_SHAPE
+    assert g(FAKE, None, None, FAKE, FAKE, FAKE, eps, 1, 8, 8, B.F32, FAKE, FAKE, None) == E_NULL
+    assert g(FAKE, None, FAKE, FAKE, FAKE, FAKE, eps, 1, 8, 8, B.F32, FAKE, None, None) == E_NULL

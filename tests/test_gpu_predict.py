@@ -1,7 +1,10 @@
 """GPU parity of paep_predict with the CPU oracle, through the C ABI.
 Small cases span several tiles and ragged tails on every kernel family and are
-checked on every row; the paper-shaped cases run at full size in the launch
-configuration the benchmark uses and are checked on seeded row samples."""
+checked on every row.  The paper-shaped cases run at full token count with as
+many layers as it takes for the launcher to choose the tile configuration and
+r split it chooses for the whole model (the choice is asserted through
+paep_predict_plan), and are checked on seeded row samples -- on every row for
+the DeepSeek-V2-Lite shape."""
 import numpy as np
 import pytest
 import torch
@@ -53,9 +56,16 @@ def _run_and_check(x, W1, W2, b1, b2, k, dtype, act="none", path="auto", rows=No
         if rep_m:
             tot_m.add(rep_m)
     print(f"{what}: path={out.path} rows={tot.rows} strict={tot.strict} exempt={tot.exempt} "
-          f"exempt_differ={tot.exempt_differ} max_err={tot.max_logit_err:.2e}*s_t | vs bf16-hidden oracle: "
-          f"strict={tot_m.strict} differ={tot_m.exempt_differ} max_err={tot_m.max_logit_err:.2e}*s_t", flush=True)
+          f"exempt_differ={tot.exempt_differ} max_err={tot.max_logit_err:.2e}*s_t prob_rel_err={tot.max_prob_rel_err:.2e} "
+          f"(vs own scores {tot.max_prob_rel_err_own:.2e}, idx = rule(own scores) on {tot.own_topk_rows} rows) | "
+          f"vs bf16-hidden oracle: strict={tot_m.strict} differ={tot_m.exempt_differ} "
+          f"max_err={tot_m.max_logit_err:.2e}*s_t prob_rel_err={tot_m.max_prob_rel_err:.2e}", flush=True)
+    assert tot.own_topk_rows == tot.rows
     return out, tot, tot_m
+
+
+def _plan(T, d, r, E, k, L):
+    return B.predict_plan(B.make_desc(T, d, r, E, k, L, B.BF16))
 
 
 # ------------------------------------------------------------------ toy / simple path
@@ -175,6 +185,25 @@ def test_prefill_large_tile_configs_with_ragged_tail(E, k, r, d, L, T):
     assert out.path == "prefill"
 
 
+@pytest.mark.parametrize("E,k,r,d,L,T,tile,groups,cpg", [
+    # at least 256 token tiles: every workgroup walks all of r by itself, several chunks of it --
+    # the configuration a whole model's worth of layers runs in
+    (64, 6, 1024, 64, 8, 8229, "256x256", 1, 4),
+    (128, 8, 1024, 64, 8, 8229, "256x256 wide", 1, 4),
+    (256, 8, 512, 64, 8, 8229, "256x128", 1, 4),
+    (200, 12, 640, 128, 8, 8229, "256x128", 1, 5),
+    # ... and with long rows (d = 4096) r split over two workgroups per tile, again at >= 256 tiles:
+    # score tiles through the workspace, last arriver adds them (release/acquire through one thread's fences)
+    (64, 6, 512, 4096, 8, 8300, "256x256", 2, 1),
+])
+def test_prefill_many_tiles_every_row(E, k, r, d, L, T, tile, groups, cpg):
+    plan = _plan(T, d, r, E, k, L)
+    assert (plan.path, plan.tile, plan.groups, plan.chunks_per_group) == ("prefill", tile, groups, cpg), plan
+    x, W1, W2, b1, b2 = _rand_layers(170 + E + d, L=L, T=T, d=d, r=r, E=E, dtype="bf16", bias=True)
+    out, *_ = _run_and_check(x, W1, W2, b1, b2, k, "bf16", what=f"prefill many tiles E={E} r={r} d={d} {plan}")
+    assert out.path == "prefill"
+
+
 # ------------------------------------------------------------------ paper-shaped, full size, sampled rows
 def _paper_shaped(name, T, layers, n_rows, path):
     w = configs.get(name)
@@ -199,8 +228,12 @@ def test_deepseek_shaped_decode_all_layers(T):
     _paper_shaped("deepseek_v2_lite", T, range(26), T, "decode")
 
 
-def test_deepseek_shaped_prefill_all_layers_sampled():
-    _paper_shaped("deepseek_v2_lite", 4096, range(26), 24, "prefill")
+def test_deepseek_shaped_prefill_all_layers_every_row():
+    w = configs.get("deepseek_v2_lite")
+    plan = _plan(4096, w.d, w.r, w.E, w.k, w.L)
+    assert (plan.tile, plan.groups, plan.chunks_per_group) == ("256x256", 1, 8), plan
+    out, tot, tot_m, _ = _paper_shaped("deepseek_v2_lite", 4096, range(26), 4096, "prefill")
+    assert tot.rows == 26 * 4096
 
 
 @pytest.mark.parametrize("T", [1, 16, 64])
@@ -209,7 +242,12 @@ def test_qwen3_shaped_decode(T):
 
 
 def test_qwen3_shaped_prefill_sampled():
-    _paper_shaped("qwen3_30b_a3b", 8192, [0, 17, 30, 47], 32, "prefill")
+    """Eight layers: 256 token tiles, which makes the launcher choose what it chooses for all 48."""
+    w = configs.get("qwen3_30b_a3b")
+    layers = [0, 6, 13, 17, 24, 30, 41, 47]
+    full, part = _plan(8192, w.d, w.r, w.E, w.k, w.L), _plan(8192, w.d, w.r, w.E, w.k, len(layers))
+    assert full == part and (part.tile, part.groups, part.chunks_per_group) == ("256x256 wide", 1, 8), (full, part)
+    _paper_shaped("qwen3_30b_a3b", 8192, layers, 48, "prefill")
 
 
 @pytest.mark.parametrize("T", [1, 32])
@@ -218,11 +256,19 @@ def test_phi_shaped_decode(T):
 
 
 def test_phi_shaped_prefill_sampled():
-    _paper_shaped("phi_mini_moe", 8192, [0, 9, 20, 31], 32, "prefill")
+    w = configs.get("phi_mini_moe")
+    layers = [0, 4, 9, 13, 20, 24, 27, 31]
+    full, part = _plan(8192, w.d, w.r, w.E, w.k, w.L), _plan(8192, w.d, w.r, w.E, w.k, len(layers))
+    assert full == part and part.groups == 2, (full, part)
+    _paper_shaped("phi_mini_moe", 8192, layers, 32, "prefill")
 
 
 def test_stress_shaped_prefill_sampled_with_near_ties():
-    out, tot, tot_m, lays = _paper_shaped("stress", 32768, [0], 64, "prefill")
+    """Two layers of 32768 tokens: 256 token tiles, the launcher's choice for all 48 layers."""
+    w = configs.get("stress")
+    full, part = _plan(32768, w.d, w.r, w.E, w.k, w.L), _plan(32768, w.d, w.r, w.E, w.k, 2)
+    assert full == part and (part.tile, part.groups, part.chunks_per_group) == ("256x128", 1, 32), (full, part)
+    out, tot, tot_m, lays = _paper_shaped("stress", 32768, [0, 47], 64, "prefill")
     assert lays[0].tie_rows.size == 328
     # the planted rows sit inside the tolerance band; they must still be valid selections
     assert tot.exempt > 0
@@ -242,7 +288,7 @@ def _check_output_properties(out, E, k):
 
 
 @pytest.mark.parametrize("name,T", [("deepseek_v2_lite", 4096), ("deepseek_v2_lite", 64), ("qwen3_30b_a3b", 8192),
-                                    ("phi_mini_moe", 8192)])
+                                    ("phi_mini_moe", 8192), ("stress", 32768)])
 def test_full_size_outputs_have_the_required_properties_and_feed_grouping(name, T):
     """All layers, the benchmark's launch configuration, random weights generated on the device; every row of the
     output is checked for the properties above, and grouping/scoring of it for their conservation laws."""
@@ -297,9 +343,104 @@ def test_counted_predict_adds_the_histogram_of_its_selections(path, T, d, r, E, 
     for l in range(L):
         hist = torch.bincount(out.idx[l].flatten().to(torch.int64), minlength=E).to(torch.int32)
         assert torch.equal(counts[l], 3 + 2 * hist), f"layer {l}"
-    # against the oracle where selection is unambiguous (fp32: every row is strict)
-    if dtype == "f32":
-        for l in range(L):
-            idx_o, _, _ = oracle.predict(x[l], W1[l], W2[l], k, want_logits=False)
-            want = oracle.group_by_expert(idx_o, E)[0]
-            assert np.array_equal((counts[l].cpu().numpy() - 3) // 2, want)
+    # against the oracle: its own selection on the rows where the selection is unambiguous (strict rows:
+    # every gap among its top k+1 scores above the tolerance; in fp32 that is every row), the kernel's
+    # selection on the others (those rows are checked for validity by the parity tests)
+    tol = parity.TOL_MODEL if dtype == "bf16" else parity.TOL["f32"]
+    n_strict = 0
+    for l in range(L):
+        idx_o, _, z_o = oracle.predict(x[l], W1[l], W2[l], k, round_h=(dtype == "bf16"))
+        zs = -np.sort(-z_o, axis=1)
+        s_t = np.abs(z_o).max(axis=1)
+        strict = (zs[:, :min(k, E - 1)] - zs[:, 1:min(k, E - 1) + 1] >= tol * s_t[:, None]).all(axis=1)
+        n_strict += int(strict.sum())
+        mixed = np.where(strict[:, None], idx_o, out.idx[l].cpu().numpy())
+        want = oracle.group_by_expert(mixed, E)[0]
+        assert np.array_equal((counts[l].cpu().numpy() - 3) // 2, want), f"layer {l}"
+    assert n_strict > 0.3 * L * T
+
+
+# ------------------------------------------------------------------ confidence outputs (sections 6 and 4.4)
+@pytest.mark.parametrize("path,T,d,r,E,k,L,dtype", [
+    ("simple", 37, 72, 40, 13, 5, 2, "f32"), ("simple", 9, 64, 128, 40, 32, 1, "f32"),
+    ("decode", 7, 256, 128, 40, 8, 3, "bf16"), ("decode", 64, 256, 128, 250, 12, 2, "bf16"),
+    ("prefill", 300, 128, 384, 64, 6, 2, "bf16"), ("prefill", 700, 128, 256, 200, 15, 3, "bf16"),
+    ("prefill", 8300, 64, 512, 128, 8, 4, "bf16"), ("prefill", 150, 128, 128, 8, 8, 1, "bf16"),
+])
+def test_confidence_outputs_match_the_oracle(path, T, d, r, E, k, L, dtype):
+    x, W1, W2, _, _ = _rand_layers(1300 + T + k, L=L, T=T, d=d, r=r, E=E, dtype=dtype)
+    xs, a, b = _dev(x, dtype), _dev(W1, dtype), _dev(W2, dtype)
+    base = B.predict(xs, a, b, k, path=path, want_logits=True)
+    outs = {m: B.predict(xs, a, b, k, path=path, prob=m, want_margin=True) for m in ("softmax", "softmax_topk", "sigmoid")}
+    torch.cuda.synchronize()
+    tol = parity.TOL["bf16" if dtype == "bf16" else "f32"]
+    for m, o in outs.items():
+        assert o.path == path, (m, o.path)
+        assert torch.equal(o.idx, base.idx), m                    # all three scores are monotone: same selection
+        assert torch.equal(o.margin, outs["softmax"].margin)
+    assert torch.equal(outs["softmax"].probs, base.probs)
+    zg = base.logits.cpu().numpy()
+    idx = base.idx.cpu().numpy()
+    for l in range(L):
+        # (a) sharp, against the kernel's own scores: definitions evaluated in float64 on what it selected from
+        soft_o, sig_o, margin_o = oracle.confidence_outputs(zg[l].astype(np.float64), idx[l])
+        for name, want in (("softmax_topk", soft_o), ("sigmoid", sig_o)):
+            got = outs[name].probs[l].cpu().numpy().astype(np.float64)
+            assert np.abs(got - want).max() <= parity.PROB_TOL_OWN * np.abs(want).max() + 1e-30, (name, l)
+            assert (np.abs(got - want) <= parity.PROB_TOL_OWN * want + 1e-12).all(), (name, l)
+        mg = outs["softmax"].margin[l].cpu().numpy()
+        if k < E:
+            own = -np.sort(-zg[l], axis=1)
+            assert np.array_equal(mg, own[:, k - 1] - own[:, k]), f"margin layer {l}"      # one fp32 subtraction
+        else:
+            assert np.isinf(mg).all() and (mg > 0).all()
+        # (b) against the oracle's own scores, within what the score tolerance allows
+        idx_r, _, z_r = oracle.predict(x[l], W1[l], W2[l], k)
+        _, _, margin_r = oracle.confidence_outputs(z_r, idx_r)
+        delta = tol * np.abs(z_r).max(axis=1)
+        if k < E:
+            assert (np.abs(mg - margin_r) <= 2 * delta + 1e-6).all(), f"margin vs oracle, layer {l}"
+        soft_r, sig_r, _ = oracle.confidence_outputs(z_r, idx[l])          # the oracle's scores at the kernel's selection
+        got = outs["softmax_topk"].probs[l].cpu().numpy()
+        assert (np.abs(got - soft_r) <= (np.expm1(2 * delta)[:, None] + 2e-5) * soft_r + 1e-30).all()
+        got = outs["sigmoid"].probs[l].cpu().numpy()
+        assert (np.abs(got - sig_r) <= (np.expm1(delta)[:, None] + 2e-5) * sig_r + 1e-30).all()
+    assert np.allclose(outs["softmax_topk"].probs.sum(dim=-1).cpu().numpy(), 1.0, atol=1e-5)
+
+
+def test_margin_on_the_prefill_path_needs_room_for_one_more_candidate():
+    x, W1, W2, _, _ = _rand_layers(1400, L=1, T=200, d=128, r=128, E=64, dtype="bf16")
+    xs, a, b = _dev(x, "bf16"), _dev(W1, "bf16"), _dev(W2, "bf16")
+    with pytest.raises(B.PaepError) as e:
+        B.predict(xs, a, b, 16, path="prefill", want_margin=True)
+    assert e.value.status == 8                                          # PAEP_ERR_UNSUPPORTED
+    o = B.predict(xs, a, b, 16, want_margin=True, want_logits=True)      # AUTO falls back to a family that can
+    torch.cuda.synchronize()
+    assert o.path == "simple"
+    own = -np.sort(-o.logits[0].cpu().numpy(), axis=1)
+    assert np.array_equal(o.margin[0].cpu().numpy(), own[:, 15] - own[:, 16])
+
+
+# ------------------------------------------------------------------ BatchNorm folded into the first layer (section 4.3)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_fold_batchnorm_matches_the_oracle_and_feeds_predict(dtype):
+    g = np.random.default_rng(77)
+    L, T, d, r, E, k = 2, 50, 72, 40, 13, 5
+    x, W1, W2, b1, _ = _rand_layers(78, L=L, T=T, d=d, r=r, E=E, dtype=dtype, bias=True)
+    gamma = (1 + 0.3 * g.standard_normal((L, r))).astype(np.float32)
+    beta = (0.2 * g.standard_normal((L, r))).astype(np.float32)
+    mean = (0.5 * g.standard_normal((L, r))).astype(np.float32)
+    var = (0.5 + g.random((L, r))).astype(np.float32)
+    f32 = lambda v: torch.from_numpy(v).cuda()
+    W1f, b1f = B.fold_batchnorm(_dev(W1, dtype), _dev(b1, dtype), f32(gamma), f32(beta), f32(mean), f32(var), 1e-5)
+    W1n, _ = B.fold_batchnorm(_dev(W1, dtype), None, f32(gamma), f32(beta), f32(mean), f32(var), 1e-5)
+    torch.cuda.synchronize()
+    assert torch.equal(W1n, W1f)
+    ulp = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -22                   # one rounding to storage + fp32 arithmetic
+    for l in range(L):
+        Wo, bo = oracle.fold_batchnorm(W1[l], b1[l], gamma[l], beta[l], mean[l], var[l], 1e-5)
+        assert (np.abs(W1f[l].float().cpu().numpy() - Wo) <= ulp * np.abs(Wo) + 1e-30).all()
+        assert (np.abs(b1f[l].float().cpu().numpy() - bo) <= ulp * np.abs(bo) + 1e-6).all()
+    # Architecture 1 end to end: folded weights + exact GELU through the predictor, against the oracle on the same weights
+    Wh, bh = W1f.float().cpu().numpy(), b1f.float().cpu().numpy()
+    _run_and_check(x, Wh, W2, bh, None, k, dtype, act="gelu", path="simple", what=f"arch-1 folded {dtype}")

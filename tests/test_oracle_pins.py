@@ -444,3 +444,87 @@ def test_confidence_select_hand_cases_and_monotonicity():
         gap = zs[:, 2] - zs[:, 3]
         clear = np.abs(gap - tau) > 1e-4
         assert np.array_equal((k_row == 3)[clear], (gap >= tau)[clear])
+
+
+# ---------------------------------------------------------------- confidence outputs (sections 6 and 4.4)
+def _conf_case(seed=0, T=40, d=24, r=16, E=12, k=4):
+    g = np.random.default_rng(seed)
+    x = g.standard_normal((T, d)).astype(np.float32)
+    W1 = (g.standard_normal((r, d)) / np.sqrt(d)).astype(np.float32)
+    W2 = (g.standard_normal((E, r)) * 2 / np.sqrt(r)).astype(np.float32)
+    idx, probs, z = oracle.predict(x, W1, W2, k)
+    return x, W1, W2, idx, probs, z
+
+
+def test_confidence_softmax_over_the_selection_sums_to_one_and_is_the_library_softmax_of_those_scores():
+    import scipy.special
+    _, _, _, idx, probs, z = _conf_case()
+    soft, _, _ = oracle.confidence_outputs(z, idx)
+    assert np.allclose(soft.sum(axis=1), 1.0, rtol=0, atol=1e-14)
+    sel = np.take_along_axis(z, idx.astype(np.int64), axis=1)
+    assert np.allclose(soft, scipy.special.softmax(sel, axis=1), rtol=1e-13, atol=0)
+    # and it is the all-expert softmax (eq. 1) renormalised over the selection
+    p_all = scipy.special.softmax(z, axis=1)
+    p_sel = np.take_along_axis(p_all, idx.astype(np.int64), axis=1)
+    assert np.allclose(soft, p_sel / p_sel.sum(axis=1, keepdims=True), rtol=1e-12, atol=0)
+    assert (np.diff(soft, axis=1) <= 0).all()                      # descending like the scores
+
+
+def test_confidence_sigmoid_is_the_library_sigmoid():
+    import scipy.special
+    import torch
+    _, _, _, idx, _, z = _conf_case(1)
+    _, sig, _ = oracle.confidence_outputs(z, idx)
+    sel = np.take_along_axis(z, idx.astype(np.int64), axis=1)
+    assert np.allclose(sig, scipy.special.expit(sel), rtol=1e-14, atol=0)
+    assert np.allclose(sig, torch.sigmoid(torch.from_numpy(sel)).numpy(), rtol=1e-14, atol=0)
+    assert np.allclose(oracle.confidence_outputs(np.zeros((1, 3)), np.array([[0, 1]]))[1], 0.5)
+
+
+def test_confidence_margin_is_the_gap_after_the_selection():
+    x, W1, W2, idx, probs, z = _conf_case(2, k=4)
+    _, _, margin = oracle.confidence_outputs(z, idx)
+    # independent route: predict one expert more; the margin is the gap between its last two scores,
+    # and (one softmax normaliser per row) the log of the ratio of their probabilities
+    idx5, probs5, _ = oracle.predict(x, W1, W2, 5)
+    gap = z[np.arange(z.shape[0]), idx5[:, 3]] - z[np.arange(z.shape[0]), idx5[:, 4]]
+    assert np.array_equal(margin, gap)
+    assert np.allclose(margin, np.log(probs5[:, 3].astype(np.float64) / probs5[:, 4]), rtol=0, atol=1e-5)
+    assert (margin >= 0).all()
+    # brute force on the full ordering
+    for t in range(z.shape[0]):
+        order = sorted(range(z.shape[1]), key=lambda e: (-z[t, e], e))
+        assert margin[t] == z[t, order[3]] - z[t, order[4]]
+    # hand case, an exact tie at the boundary, and k = E
+    zz = np.array([[3.0, 1.0, 2.0, 0.5], [1.0, 1.0, 1.0, 0.0]])
+    assert oracle.confidence_outputs(zz, np.array([[0, 2], [0, 1]]))[2].tolist() == [1.0, 0.0]
+    assert np.isinf(oracle.confidence_outputs(zz, np.array([[0, 2, 1, 3], [0, 1, 2, 3]]))[2]).all()
+
+
+# ---------------------------------------------------------------- BatchNorm folding (section 4.3, Architecture 1)
+def test_batchnorm_folds_into_the_first_layer():
+    import torch
+    import torch.nn.functional as F
+    g = np.random.default_rng(5)
+    T, d, r, E, k = 30, 20, 14, 9, 3
+    x = g.standard_normal((T, d)).astype(np.float32)
+    W1 = (g.standard_normal((r, d)) / np.sqrt(d)).astype(np.float32)
+    b1 = (0.2 * g.standard_normal(r)).astype(np.float32)
+    W2 = (g.standard_normal((E, r)) / np.sqrt(r)).astype(np.float32)
+    gamma, beta = 1 + 0.3 * g.standard_normal(r), 0.2 * g.standard_normal(r)
+    mean, var, eps = 0.5 * g.standard_normal(r), 0.5 + g.random(r), 1e-5
+    W1f, b1f = oracle.fold_batchnorm(W1, b1, gamma, beta, mean, var, eps)
+    # the library's BatchNorm (inference form) on u = W1 x + b1, in float64
+    t64 = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    u = t64(x) @ t64(W1).T + t64(b1)
+    bn = F.batch_norm(u, t64(mean), t64(var), weight=t64(gamma), bias=t64(beta), training=False, eps=eps)
+    assert np.allclose(x.astype(np.float64) @ W1f.T + b1f, bn.numpy(), rtol=1e-12, atol=1e-12)
+    # the whole Architecture-1 block through the oracle with folded weights = Linear, BN, exact GELU, Linear.
+    # (the oracle takes float32 storage, so fold first, then round once, and feed both sides the same weights)
+    W1s, b1s = W1f.astype(np.float32), b1f.astype(np.float32)
+    _, _, z = oracle.predict(x, W1s, W2, k, b1=b1s, act=oracle.ACT_GELU)
+    want = F.gelu(t64(x) @ t64(W1s).T + t64(b1s), approximate="none") @ t64(W2).T
+    assert np.allclose(z, want.numpy(), rtol=1e-12, atol=1e-12)
+    # no bias given = zero bias; unit statistics = identity
+    W1n, b1n = oracle.fold_batchnorm(W1, None, np.ones(r), np.zeros(r), np.zeros(r), np.ones(r), 0.0)
+    assert np.array_equal(W1n, W1.astype(np.float64)) and not b1n.any()
