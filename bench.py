@@ -14,8 +14,13 @@ roofline of the dominant kernel (measured live with HIP events around the
 predict launches of the timed steps), and the CPU oracle timed on a bounded
 sample of the same workload (a baseline, not a target).
 
+The default run reports the workload's prefill size as the headline and, under
+"also", its decode sizes (each with its own HBM roofline) and the prefill size
+again with the over-provisioned prediction width the paper evaluates
+(section 5.2), all on the same weight banks.
+
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--T tokens] [--k-pred K'] [--no-cpu]
-                    [--sweep] [--pipeline] [--copy-probe-mib N]
+                    [--only] [--pipeline] [--copy-probe-mib N]
 """
 import argparse
 import json
@@ -74,10 +79,42 @@ def algorithmic_work(w, T, k=None):
     return flops, nbytes
 
 
+class Banks:
+    """The workload's predictor weights on the device: several independently generated banks (a step uses
+    one and the next step the next, so that no step finds its weights in the Infinity Cache), the router
+    the labels are drawn from (bank 0's), and the biases.  Shared by every token count that is timed."""
+
+    def __init__(self, w, n_banks=None):
+        import numpy as np
+        import torch
+        from paper_2511_10676_amd import datagen
+        L = w.L
+        bank_bytes = 2 * L * w.r * (w.d + w.E)
+        if n_banks is None:
+            n_banks = max(2, -(-2 * MALL_BYTES // bank_bytes) + 1)
+        self.n_banks = n_banks
+        self.to_dev = to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(torch.bfloat16).cuda()
+        self.W1, self.W2, self.routers, b2s = [], [], [], []
+        W1_0, W2_0 = [], []
+        for l in range(L):
+            W1_0.append(datagen.make_w1(w, l)); W2_0.append(datagen.make_w2(w, l))
+            self.routers.append(datagen.make_router(w, l, W1_0[-1], W2_0[-1]))
+            b2 = datagen.make_b2(w, l)
+            if b2 is not None:
+                b2s.append(b2)
+        self.b2_host = b2s
+        self.b2 = to_dev(np.stack(b2s)) if b2s else None
+        self.W1.append(to_dev(np.stack(W1_0))); self.W2.append(to_dev(np.stack(W2_0)))
+        del W1_0, W2_0
+        for bank in range(1, n_banks):
+            self.W1.append(to_dev(np.stack([datagen.make_w1(w, l, bank) for l in range(L)])))
+            self.W2.append(to_dev(np.stack([datagen.make_w2(w, l, bank) for l in range(L)])))
+
+
 class Runner:
     """Device buffers for one workload at one token count, and the step."""
 
-    def __init__(self, w, T, n_banks=None, k_pred=None, pipelined=False):
+    def __init__(self, w, T, banks, k_pred=None, pipelined=False):
         import numpy as np
         import torch
         from paper_2511_10676_amd import binding as B
@@ -85,36 +122,20 @@ class Runner:
         self.B, self.torch, self.w, self.T = B, torch, w, T
         self.k_pred = kp = k_pred or w.k            # experts predicted per token (> w.k: over-provisioning, section 4.1)
         L = w.L
-        bank_bytes = 2 * L * w.r * (w.d + w.E)
-        if n_banks is None:
-            n_banks = max(2, -(-2 * MALL_BYTES // bank_bytes) + 1)
-        self.n_banks = n_banks
-        to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(torch.bfloat16).cuda()
-        t0 = time.time()
-        xs, refs, b2s = [], [], []
-        self.W1, self.W2 = [], []
-        W1_0, W2_0 = [], []
+        self.n_banks = n_banks = banks.n_banks
+        self.W1, self.W2, self.b2 = banks.W1, banks.W2, banks.b2
+        xs, refs = [], []
         for l in range(L):
-            W1_0.append(datagen.make_w1(w, l)); W2_0.append(datagen.make_w2(w, l))
             x = datagen.make_x(w, l, T)
-            b2 = datagen.make_b2(w, l)
-            Wg = datagen.make_router(w, l, W1_0[-1], W2_0[-1])
-            refs.append(datagen.router_labels(Wg, x, b2, w.k))
+            refs.append(datagen.router_labels(banks.routers[l], x, banks.b2_host[l] if banks.b2_host else None, w.k))
             xs.append(x)
-            if b2 is not None:
-                b2s.append(b2)
-        self.x = to_dev(np.stack(xs))
+        self.x = banks.to_dev(np.stack(xs))
         self.ref = torch.from_numpy(np.stack(refs)).cuda()
-        self.b2 = to_dev(np.stack(b2s)) if b2s else None
-        self.W1.append(to_dev(np.stack(W1_0))); self.W2.append(to_dev(np.stack(W2_0)))
-        del xs, W1_0, W2_0
-        for bank in range(1, n_banks):
-            self.W1.append(to_dev(np.stack([datagen.make_w1(w, l, bank) for l in range(L)])))
-            self.W2.append(to_dev(np.stack([datagen.make_w2(w, l, bank) for l in range(L)])))
-        self.setup_s = time.time() - t0
+        del xs
         dev = self.x.device
         desc = B.make_desc(T, w.d, w.r, w.E, kp, L, B.BF16)
         self.path = B.resolve_path(desc)
+        self.plan = B.predict_plan(desc)
         ws = B.predict_workspace_bytes(desc)
         self.ws = torch.empty(max(ws, 16), dtype=torch.uint8, device=dev)
         # Pipelined mode: two sets of result buffers and two streams, predict of step i+1 (stream A)
@@ -205,7 +226,10 @@ class Runner:
         prof = self.B.activation_profile(self.grps[self.last].counts)   # untimed: popularity skew of what was just predicted
         self.torch.cuda.synchronize()
         self.entropy0 = round(float(prof.entropy[0]), 4)
-        return {"T": T, "path": self.path, "ms_per_step": round(ms_step, 4),
+        return {"T": T, "k_pred": self.k_pred, "path": self.path,
+                "launch": (f"{self.plan.tile} tiles, {self.plan.groups} workgroup(s) per token tile"
+                           if self.path == "prefill" else "r in slices of 64 per workgroup + finalize"),
+                "ms_per_step": round(ms_step, 4),
                 "value": round(T * w.L / (ms_step * 1e-3), 1), "roofline": roof,
                 "score_layer0": self.cnts[self.last][0].cpu().numpy().tolist(), "weight_banks": self.n_banks,
                 "timing": self.stats}
@@ -244,26 +268,48 @@ def device_ceilings(torch, B):
     return out
 
 
-def cpu_baseline(w, T, budget_s=20.0):
-    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
-    import numpy as np
+def _oracle_pass(w, inputs):
     import oracle
-    from paper_2511_10676_amd import datagen
-    mac_per_token = w.r * (w.d + w.E)
-    est_rate = 1.5e9 * oracle.num_threads()                 # MAC/s guess used only to size the sample (~15 s of work)
-    tokens = int(max(1, min(T * w.L, budget_s * est_rate / mac_per_token)))
-    layers = max(1, min(w.L, tokens // T)) if T <= tokens else 1
-    Ts = min(T, tokens // layers)
-    inputs = [datagen.make_layer(w, l, Ts) for l in range(layers)]
     t0 = time.perf_counter()
     for lay in inputs:
         idx, probs, _ = oracle.predict(lay.x, lay.W1, lay.W2, w.k, b2=lay.b2, want_logits=False)
         oracle.group_by_expert(idx, w.E)
         oracle.score(idx, lay.ref, w.E)
-    dt = time.perf_counter() - t0
-    return {"value": round(layers * Ts / dt, 1), "unit": "tokens*layers/s", "cores": oracle.num_threads(),
-            "kind": "oracle", "seconds": round(dt, 2),
-            "sample": f"layers 0..{layers - 1} of {w.L}, first {Ts} of {T} tokens each: predict + group + score"}
+    return time.perf_counter() - t0
+
+
+def cpu_baseline(w, T, budget_s=16.0, budget_1t_s=5.0):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: with every host thread
+    OpenMP gives it, and on one thread (a smaller sample of the same rows)."""
+    import ctypes
+    import oracle
+    from paper_2511_10676_amd import datagen
+    mac_per_token = w.r * (w.d + w.E)
+    threads = oracle.num_threads()
+    est_rate = 1.5e9 * threads                              # MAC/s guess used only to size the sample
+    tokens = int(max(1, min(T * w.L, budget_s * est_rate / mac_per_token)))
+    layers = max(1, min(w.L, tokens // T)) if T <= tokens else 1
+    Ts = min(T, tokens // layers)
+    inputs = [datagen.make_layer(w, l, Ts) for l in range(layers)]
+    dt = _oracle_pass(w, inputs)
+    out = {"value": round(layers * Ts / dt, 1), "unit": "tokens*layers/s", "cores": threads,
+           "kind": "oracle", "seconds": round(dt, 2),
+           "sample": f"layers 0..{layers - 1} of {w.L}, first {Ts} of {T} tokens each: predict + group + score"}
+    # one thread: the OpenMP runtime the oracle was built against is told to use one (the oracle is not changed)
+    try:
+        omp = ctypes.CDLL("libgomp.so.1")
+        T1 = int(max(1, min(Ts, budget_1t_s * 1.5e9 / mac_per_token)))
+        lay1 = [datagen.make_layer(w, 0, T1)]
+        omp.omp_set_num_threads(1)
+        try:
+            dt1 = _oracle_pass(w, lay1)
+        finally:
+            omp.omp_set_num_threads(threads)
+        out["single_thread"] = {"value": round(T1 / dt1, 1), "unit": "tokens*layers/s", "cores": 1,
+                                "seconds": round(dt1, 2), "sample": f"layer 0, first {T1} of {T} tokens"}
+    except OSError:
+        out["single_thread"] = None
+    return out
 
 
 def main():
@@ -281,7 +327,10 @@ def main():
                          "at prefill sizes, slower at decode sizes, and the predict kernel is then timed under "
                          "contention)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
-    ap.add_argument("--sweep", action="store_true", help="also time the workload's other token counts")
+    ap.add_argument("--only", action="store_true",
+                    help="time only the chosen token count (skip the workload's other token counts and the "
+                         "over-provisioned width)")
+    ap.add_argument("--sweep", action="store_true", help="accepted for compatibility: the sweep is the default")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="first run one plain device copy of this many MiB (a kernel of known traffic, for "
                          "scaling hardware byte counters collected over the same run)")
@@ -307,7 +356,8 @@ def main():
         torch.cuda.empty_cache()
     from paper_2511_10676_amd import binding as B
     ceilings = device_ceilings(torch, B)
-    run = Runner(w, T, k_pred=args.k_pred or None, pipelined=args.pipeline)
+    banks = Banks(w)
+    run = Runner(w, T, banks, k_pred=args.k_pred or None, pipelined=args.pipeline)
     main_rep = run.report(args.steps, args.warmup)
     line = {
         "metric": "predicted tokens*layers per second",
@@ -316,7 +366,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}-shaped: L={w.L} d={w.d} r={w.r} E={w.E} k={w.k}, T={T} tokens/layer "
-                               f"({main_rep['path']} path), step = predict + group_by_expert + score, all layers",
+                               f"({main_rep['path']} path, {main_rep['launch']}), step = predict + group_by_expert "
+                               f"+ score, all layers",
                    "k_pred": run.k_pred,
                    "streams": ("2: group_by_expert + score of step i run beside predict of step i+1"
                                if run.pipelined else "1"),
@@ -329,12 +380,23 @@ def main():
     }
     del run
     torch.cuda.empty_cache()
-    if args.sweep:
+    if not args.only:
+        # the rest of the metric: the workload's other token counts (decode sizes: HBM roofline), then the
+        # headline size again predicting the over-provisioned width and scored against the router's k labels
         also = []
-        for T2 in list(w.decode_T) + [t for t in w.prefill_T if t != T]:
-            r2 = Runner(w, T2, k_pred=args.k_pred or None, pipelined=args.pipeline)
+        kp0 = args.k_pred or None
+        cases = [(T2, kp0) for T2 in list(w.decode_T) + list(w.prefill_T) if T2 != T]
+        if w.k_over and not args.k_pred:
+            cases.append((T, w.k_over))
+        for T2, kp in cases:
+            r2 = Runner(w, T2, banks, k_pred=kp, pipelined=args.pipeline)
             rep = r2.report(max(args.steps, 50) if T2 <= 64 else args.steps, args.warmup)
-            rep.pop("score_layer0")
+            if kp == kp0:
+                rep.pop("score_layer0")
+            else:
+                rep["score_layer0_meaning"] = (f"k_pred={kp} predicted against k={w.k} labels: exact-match rows (0 by "
+                                               "definition when the widths differ), correctly predicted experts, "
+                                               "rows whose labels are all predicted, top-1 hits")
             also.append(rep)
             del r2
             torch.cuda.empty_cache()
