@@ -357,7 +357,7 @@ def test_counted_predict_adds_the_histogram_of_its_selections(path, T, d, r, E, 
         mixed = np.where(strict[:, None], idx_o, out.idx[l].cpu().numpy())
         want = oracle.group_by_expert(mixed, E)[0]
         assert np.array_equal((counts[l].cpu().numpy() - 3) // 2, want), f"layer {l}"
-    assert n_strict > 0.3 * L * T
+    assert n_strict > 0.1 * L * T                 # the oracle's own selection decides a good share of the rows
 
 
 # ------------------------------------------------------------------ confidence outputs (sections 6 and 4.4)
