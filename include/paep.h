@@ -175,6 +175,34 @@ paep_status paep_predict_confidence(const paep_predict_desc *desc,
                                     void *workspace_dev, size_t workspace_bytes, void *stream);
 
 /*
+ * paep_predict for callers that cannot allocate device memory or carry a
+ * workspace around: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same computation, same kernels and same
+ * results as paep_predict; the workspace is a buffer of
+ * PAEP_STATIC_SCRATCH_BYTES that lives inside the library's code object, one
+ * copy per GPU, held until the process ends.  The call allocates and frees
+ * nothing (no hipMalloc, no hipFree, no allocating library routine).
+ *   - Shapes whose paep_predict_workspace_bytes exceeds
+ *     PAEP_STATIC_SCRATCH_BYTES return PAEP_ERR_WORKSPACE (16 MiB covers the
+ *     decode path of a DeepSeek-V2-Lite-sized bank up to 64 tokens and every
+ *     prefill shape that needs no r split); nothing is launched then.
+ *   - Every call on a GPU uses that GPU's one buffer, which keeps whatever the
+ *     last call left in it; the kernels overwrite (or clear with a fill kernel)
+ *     every part they later read.  Two calls that may overlap on one GPU
+ *     (different streams, or several host threads) race on it: serialise them,
+ *     or use paep_predict with a workspace each.
+ *   - The first call on a device looks up the device address of the buffer
+ *     (hipGetSymbolAddress).  paep_static_init() does that ahead of time for
+ *     the current device -- call it once per device before capturing a graph.
+ */
+#define PAEP_STATIC_SCRATCH_BYTES (16u << 20)
+paep_status paep_static_init(void);
+paep_status paep_predict_static(const paep_predict_desc *desc,
+                                const void *x_dev, const void *W1_dev, const void *W2_dev,
+                                const void *b1_dev, const void *b2_dev,
+                                int32_t *idx_dev, float *probs_dev, float *logits_dev, void *stream);
+
+/*
  * How paep_predict (want_margin = 0) or paep_predict_confidence with a margin
  * output (want_margin = 1) will run this shape.  Host only; for tests and reports.
  *   plan[0] kernel family (paep_path)

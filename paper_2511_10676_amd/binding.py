@@ -29,7 +29,10 @@ MAX_K, MAX_E = 32, 1024
 STATUS_NAMES = ["PAEP_OK", "PAEP_ERR_NULL", "PAEP_ERR_SHAPE", "PAEP_ERR_K", "PAEP_ERR_DTYPE",
                 "PAEP_ERR_ALIGN", "PAEP_ERR_WORKSPACE", "PAEP_ERR_HIP", "PAEP_ERR_UNSUPPORTED"]
 
+STATIC_SCRATCH_BYTES = 16 << 20
+
 EXPORTS = ["paep_predict_workspace_bytes", "paep_predict_resolve_path", "paep_predict_plan", "paep_predict",
+           "paep_static_init", "paep_predict_static",
            "paep_predict_counted", "paep_predict_confidence", "paep_fold_batchnorm",
            "paep_group_workspace_bytes", "paep_group_by_expert", "paep_score",
            "paep_score_rows", "paep_confidence_select", "paep_activation_profile", "paep_probe_read",
@@ -80,6 +83,10 @@ def lib() -> ctypes.CDLL:
         L.paep_predict_counted.restype = ctypes.c_int
         L.paep_predict_confidence.argtypes = [dp] + [vp] * 11 + [sz, vp]
         L.paep_predict_confidence.restype = ctypes.c_int
+        L.paep_predict_static.argtypes = [dp] + [vp] * 8 + [vp]
+        L.paep_predict_static.restype = ctypes.c_int
+        L.paep_static_init.argtypes = []
+        L.paep_static_init.restype = ctypes.c_int
         L.paep_predict_plan.argtypes = [dp, i32, ctypes.POINTER(ctypes.c_int32 * 4)]
         L.paep_predict_plan.restype = ctypes.c_int
         L.paep_fold_batchnorm.argtypes = [vp] * 6 + [ctypes.c_float] + [i32] * 4 + [vp] * 3
@@ -198,13 +205,8 @@ def predict_plan(desc: PredictDesc, want_margin: bool = False) -> Plan:
     return Plan(path, TILE_CFG.get(out[1], "?") if path == "prefill" else "", int(out[2]), int(out[3]))
 
 
-def prepare_predict(x: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, k: int, *,
-                    b1: Optional[torch.Tensor] = None, b2: Optional[torch.Tensor] = None,
-                    act: str = "none", path: str = "auto", want_logits: bool = False,
-                    out: Optional[Prediction] = None, workspace: Optional[torch.Tensor] = None,
-                    counts: Optional[torch.Tensor] = None, prob: str = "softmax",
-                    want_margin: bool = False) -> Prepared:
-    """Check and marshal one predict call; the returned object runs it (see `predict` for the arguments)."""
+def _check_predict_inputs(x, W1, W2, k, b1, b2, act, path, prob):
+    """Shape and dtype checks shared by the predict calls; returns the 3-D views and the descriptor."""
     if W1.dim() == 2:
         W1 = W1.unsqueeze(0)
     if W2.dim() == 2:
@@ -226,6 +228,17 @@ def prepare_predict(x: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, k: int,
     desc = make_desc(T, d, r, E, k, L, dt, act, path, x_layer_stride=(T * d if Lx == L and L > 1 else 0), prob=prob)
     if L == 1:
         desc.x_layer_stride = T * d
+    return x, W1, W2, desc, (L, T, E)
+
+
+def prepare_predict(x: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, k: int, *,
+                    b1: Optional[torch.Tensor] = None, b2: Optional[torch.Tensor] = None,
+                    act: str = "none", path: str = "auto", want_logits: bool = False,
+                    out: Optional[Prediction] = None, workspace: Optional[torch.Tensor] = None,
+                    counts: Optional[torch.Tensor] = None, prob: str = "softmax",
+                    want_margin: bool = False) -> Prepared:
+    """Check and marshal one predict call; the returned object runs it (see `predict` for the arguments)."""
+    x, W1, W2, desc, (L, T, E) = _check_predict_inputs(x, W1, W2, k, b1, b2, act, path, prob)
     dev = x.device
     if out is None:
         idx = torch.empty((L, T, k), dtype=torch.int32, device=dev)
@@ -288,6 +301,32 @@ def predict(x: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, k: int, *,
         prep = prepare_predict(x, W1, W2, k, b1=b1, b2=b2, act=act, path=path, want_logits=want_logits, out=out,
                                workspace=workspace, counts=counts, prob=prob, want_margin=want_margin)
     return prep(stream)
+
+
+def static_init() -> None:
+    """Bind the library's built-in scratch buffer on the current device (once per device, before graph capture)."""
+    st = lib().paep_static_init()
+    if st != 0:
+        raise PaepError(st, "paep_static_init")
+
+
+def predict_static(x: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, k: int, out: Prediction, *,
+                   b1: Optional[torch.Tensor] = None, b2: Optional[torch.Tensor] = None,
+                   act: str = "none", path: str = "auto", prob: str = "softmax", stream=None) -> Prediction:
+    """paep_predict_static: predict into caller-provided `out` buffers using the library's built-in scratch
+    buffer; nothing is allocated (shapes that need more than STATIC_SCRATCH_BYTES of workspace raise)."""
+    x, W1, W2, desc, (L, T, E) = _check_predict_inputs(x, W1, W2, k, b1, b2, act, path, prob)
+    _need_device(out.idx, out.probs, out.logits)
+    if tuple(out.idx.shape) != (L, T, k) or tuple(out.probs.shape) != (L, T, k) or out.idx.dtype != torch.int32 \
+            or out.probs.dtype != torch.float32:
+        raise ValueError("out buffers have the wrong shape or dtype")
+    if out.logits is not None and (tuple(out.logits.shape) != (L, T, E) or out.logits.dtype != torch.float32):
+        raise ValueError("logits buffer has the wrong shape or dtype")
+    st = lib().paep_predict_static(ctypes.byref(desc), _ptr(x), _ptr(W1), _ptr(W2), _ptr(b1), _ptr(b2),
+                                   _ptr(out.idx), _ptr(out.probs), _ptr(out.logits), _stream_ptr(stream))
+    if st != 0:
+        raise PaepError(st, "paep_predict_static")
+    return Prediction(out.idx, out.probs, out.logits, resolve_path(desc))
 
 
 class Grouping(NamedTuple):

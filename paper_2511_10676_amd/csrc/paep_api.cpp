@@ -5,7 +5,38 @@
 
 #include "paep_internal.h"
 
+#include <mutex>
+
+// Scratch memory of paep_predict_static: one array per GPU, allocated when the
+// code object is loaded and held until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; the device address it
+// yields (per device) is what kernels and launchers are given.
+static __device__ __align__(256) unsigned char scratch[PAEP_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_mutex;
+void* scratch_dev_ptr[MAX_DEVICES];      // device address of `scratch` on each device, once looked up
+
+// Address of the current device's copy of `scratch` (looked up once per device).
+hipError_t scratch_for_current_device(void** out)
+{
+    int dev = -1;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return err;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_dev_ptr[dev]) {
+        void* p = nullptr;
+        err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (err != hipSuccess) return err;
+        if (!p) return hipErrorInvalidSymbol;
+        scratch_dev_ptr[dev] = p;
+    }
+    *out = scratch_dev_ptr[dev];
+    return hipSuccess;
+}
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -160,6 +191,27 @@ paep_status paep_predict_confidence(const paep_predict_desc* desc,
 {
     return predict_common(desc, x_dev, W1_dev, W2_dev, b1_dev, b2_dev, idx_dev, probs_dev, logits_dev, counts_dev,
                           margin_dev, workspace_dev, workspace_bytes, stream);
+}
+
+paep_status paep_static_init(void)
+{
+    void* p = nullptr;
+    return scratch_for_current_device(&p) == hipSuccess ? PAEP_OK : PAEP_ERR_HIP;
+}
+
+paep_status paep_predict_static(const paep_predict_desc* desc,
+                                const void* x_dev, const void* W1_dev, const void* W2_dev,
+                                const void* b1_dev, const void* b2_dev,
+                                int32_t* idx_dev, float* probs_dev, float* logits_dev, void* stream)
+{
+    const paep_status st = check_desc(desc);
+    if (st != PAEP_OK) return st;
+    const size_t need = paep_predict_workspace_bytes(desc);
+    if (need > (size_t)PAEP_STATIC_SCRATCH_BYTES) return PAEP_ERR_WORKSPACE;
+    void* ws = nullptr;
+    if (scratch_for_current_device(&ws) != hipSuccess) return PAEP_ERR_HIP;
+    return predict_common(desc, x_dev, W1_dev, W2_dev, b1_dev, b2_dev, idx_dev, probs_dev, logits_dev, nullptr,
+                          nullptr, ws, (size_t)PAEP_STATIC_SCRATCH_BYTES, stream);
 }
 
 paep_status paep_predict_plan(const paep_predict_desc* desc, int32_t want_margin, int32_t plan[4])
