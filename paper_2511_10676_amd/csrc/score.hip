@@ -5,6 +5,11 @@
 // to the layer's four 64-bit counters with integer atomics (exact, hence
 // deterministic).  A first tiny launch clears the counters.  Short layers take
 // a single launch instead: one workgroup per layer, no atomics.
+// Rows reach their threads coalesced: a wave reads 64 consecutive rows of a
+// [rows][k] array as k loads of 64 consecutive ints (one 256-byte access each;
+// a lane reading its own row directly would make every lane a separate access
+// to the vector cache, which serves about one access per clock), parks them in
+// its own strip of LDS and every lane then picks up its row from there.
 #include "paep_internal.h"
 
 namespace paep {
@@ -28,11 +33,31 @@ __device__ __forceinline__ int row_width(const int32_t* __restrict__ k_row, long
     return w < 1 ? 1 : (w > k_pred ? k_pred : w);
 }
 
+// raw[j] = element j*64 + lane of a chunk of n_ints consecutive ints (0 past its end): coalesced
 template <int KM>
-__device__ __forceinline__ void load_row(const int32_t* __restrict__ p, int k, int32_t (&v)[KM])
+__device__ __forceinline__ void fetch_chunk(const int32_t* __restrict__ g, int k, int n_ints, int lane,
+                                            int32_t (&raw)[KM])
 {
 #pragma unroll
-    for (int j = 0; j < KM; ++j) v[j] = (j < k) ? p[j] : 0;
+    for (int j = 0; j < KM; ++j) raw[j] = (j < k && j * 64 + lane < n_ints) ? g[j * 64 + lane] : 0;
+}
+
+// the chunk goes through the wave's own LDS strip (64 * k ints); lane l comes out with row l of the chunk
+template <int KM>
+__device__ __forceinline__ void rows_from_chunk(int32_t* strip, int k, int lane, const int32_t (&raw)[KM],
+                                                int32_t (&row)[KM])
+{
+#pragma unroll
+    for (int j = 0; j < KM; ++j)
+        if (j < k) strip[j * 64 + lane] = raw[j];
+    // only this wave uses the strip, and a wave's LDS operations complete in order
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int j = 0; j < KM; ++j) row[j] = (j < k) ? strip[lane * k + j] : 0;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
 }
 
 template <int NW, int KM>   // 64-bit words per bitset: E <= 64 * NW; ids per row <= KM
@@ -81,70 +106,98 @@ __device__ __forceinline__ void score_vals(const int32_t (&pv)[KM], int k_pred, 
     top1 += (int)((word >> (e0 & 63)) & 1ull);
 }
 
+// chunks of 64 rows per wave: four while rows are cheap, one when the kernel is compiled for long rows
+template <int KM> struct ScoreChunks { static constexpr int value = (KM <= 8) ? 4 : 1; };
+
 template <int NW, int KM>
 __global__ __launch_bounds__(SCORE_THREADS) void score_kernel(
     const int32_t* __restrict__ idx, int k_pred, const int32_t* __restrict__ ref, int k_ref,
     int T, int E, const int32_t* __restrict__ k_row, unsigned long long* __restrict__ counters)
 {
-    const int layer = blockIdx.y;
-    const int t = blockIdx.x * SCORE_THREADS + threadIdx.x;
-    int exact = 0, hit = 0, cover = 0, top1 = 0;
-    if (t < T) {
-        int32_t pv[KM], qv[KM];
-        const int kp = row_width(k_row, (long long)layer * T + t, k_pred);
-        load_row<KM>(idx + ((long long)layer * T + t) * k_pred, kp, pv);
-        load_row<KM>(ref + ((long long)layer * T + t) * k_ref, k_ref, qv);
-        score_vals<NW, KM>(pv, kp, qv, k_ref, E, exact, hit, cover, top1);
+    __shared__ int32_t strips[SCORE_THREADS / 64][64 * KM];
+    __shared__ int part[SCORE_THREADS / 64][4];
+    const int layer = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int v[4] = {0, 0, 0, 0};                                // exact, hits, cover, top1 of this lane's rows (<= 4 * 32 each)
+#pragma unroll 1
+    for (int c = 0; c < ScoreChunks<KM>::value; ++c) {
+        const int t0 = blockIdx.x * (SCORE_THREADS * ScoreChunks<KM>::value) + (c * (SCORE_THREADS / 64) + wave) * 64;   // first row of the chunk
+        if (t0 >= T) break;                                 // wave-uniform
+        const int rows = (T - t0 < 64) ? T - t0 : 64;
+        int32_t rp[KM], rq[KM], pv[KM], qv[KM];
+        fetch_chunk<KM>(idx + ((long long)layer * T + t0) * k_pred, k_pred, rows * k_pred, lane, rp);
+        fetch_chunk<KM>(ref + ((long long)layer * T + t0) * k_ref, k_ref, rows * k_ref, lane, rq);
+        rows_from_chunk<KM>(strips[wave], k_pred, lane, rp, pv);
+        rows_from_chunk<KM>(strips[wave], k_ref, lane, rq, qv);
+        const int t = t0 + lane;
+        if (t < T) {
+            const int kp = row_width(k_row, (long long)layer * T + t, k_pred);
+            score_vals<NW, KM>(pv, kp, qv, k_ref, E, v[0], v[1], v[2], v[3]);
+        }
     }
-    // wave reduction, then one atomic per wave and counter
-    int packed_small = exact | (cover << 8) | (top1 << 16);    // each <= 64 after the reduction
+    // wave reduction, workgroup reduction through LDS, then one atomic per workgroup and counter
+    // (64-bit integer atomics: exact, so the order they land in does not matter)
 #pragma unroll
-    for (int m = 1; m < 64; m <<= 1) {
-        packed_small += __shfl_xor(packed_small, m, 64);
-        hit += __shfl_xor(hit, m, 64);
-    }
-    if ((threadIdx.x & 63) == 0) {
-        unsigned long long* c = counters + (long long)layer * 4;
-        const int ex = packed_small & 0xFF, cv = (packed_small >> 8) & 0xFF, t1 = (packed_small >> 16) & 0xFF;
-        if (ex) atomicAdd(&c[0], (unsigned long long)ex);
-        if (hit) atomicAdd(&c[1], (unsigned long long)hit);
-        if (cv) atomicAdd(&c[2], (unsigned long long)cv);
-        if (t1) atomicAdd(&c[3], (unsigned long long)t1);
+    for (int m = 1; m < 64; m <<= 1)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) v[c] += __shfl_xor(v[c], m, 64);
+    if (lane == 0)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) part[wave][c] = v[c];
+    __syncthreads();
+    if (threadIdx.x < 4) {
+        unsigned long long sum = 0;
+        for (int w = 0; w < SCORE_THREADS / 64; ++w) sum += (unsigned long long)part[w][threadIdx.x];
+        if (sum) atomicAdd(&counters[(long long)layer * 4 + threadIdx.x], sum);
     }
 }
 
 // Up to LAYER_MAX_T tokens per layer: one workgroup per layer walks all rows,
 // adds up inside the workgroup and stores the four counters -- one launch, no
 // clearing pass and no atomics.
-static constexpr int LAYER_THREADS = 1024;
 static constexpr int LAYER_MAX_T = 1 << 12;
 
+// waves per workgroup: the LDS strips (64 * KM ints per wave) stay at 32 KB
+template <int KM> struct LayerWaves { static constexpr int value = (KM <= 8) ? 16 : (KM <= 16 ? 8 : 4); };
+
 template <int NW, int KM>
-__global__ __launch_bounds__(LAYER_THREADS) void score_layer_kernel(
+__global__ __launch_bounds__(LayerWaves<KM>::value * 64) void score_layer_kernel(
     const int32_t* __restrict__ idx, int k_pred, const int32_t* __restrict__ ref, int k_ref,
     int T, int E, const int32_t* __restrict__ k_row, unsigned long long* __restrict__ counters)
 {
-    __shared__ int part[LAYER_THREADS / 64][4];
-    const int layer = blockIdx.x, tid = threadIdx.x;
+    constexpr int WAVES = LayerWaves<KM>::value;
+    __shared__ int32_t strips[WAVES][64 * KM];
+    __shared__ int part[WAVES][4];
+    const int layer = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int v[4] = {0, 0, 0, 0};                                // exact, hits, cover, top1; each < 2^31 (T*k bounded by the caller)
-    // RU rows per thread at a time, all their loads issued before the first is used
-    constexpr int RU = (KM <= 8) ? 4 : 1;
-    for (int t0 = tid; t0 < T; t0 += LAYER_THREADS * RU) {
-        int32_t pv[RU][KM], qv[RU][KM];
-        int kp[RU];
+    // a wave takes chunks of 64 rows, RU chunks at a time with all their loads issued before the first is used
+    constexpr int RU = (NW > 4) ? 1 : (KM <= 8 ? 4 : (KM <= 16 ? 2 : 1));
+    const int32_t* pl = idx + (long long)layer * T * k_pred;
+    const int32_t* ql = ref + (long long)layer * T * k_ref;
+    for (int c0 = wave; c0 * 64 < T; c0 += WAVES * RU) {
+        int32_t rp[RU][KM], rq[RU][KM];
 #pragma unroll
         for (int u = 0; u < RU; ++u) {
-            const int t = t0 + u * LAYER_THREADS;
-            kp[u] = k_pred;
-            if (t < T) {
-                kp[u] = row_width(k_row, (long long)layer * T + t, k_pred);
-                load_row<KM>(idx + ((long long)layer * T + t) * k_pred, kp[u], pv[u]);
-                load_row<KM>(ref + ((long long)layer * T + t) * k_ref, k_ref, qv[u]);
+            const int t0 = (c0 + u * WAVES) * 64;
+            if (t0 < T) {                                   // wave-uniform
+                const int rows = (T - t0 < 64) ? T - t0 : 64;
+                fetch_chunk<KM>(pl + (long long)t0 * k_pred, k_pred, rows * k_pred, lane, rp[u]);
+                fetch_chunk<KM>(ql + (long long)t0 * k_ref, k_ref, rows * k_ref, lane, rq[u]);
             }
         }
 #pragma unroll
-        for (int u = 0; u < RU; ++u)
-            if (t0 + u * LAYER_THREADS < T) score_vals<NW, KM>(pv[u], kp[u], qv[u], k_ref, E, v[0], v[1], v[2], v[3]);
+        for (int u = 0; u < RU; ++u) {
+            const int t0 = (c0 + u * WAVES) * 64;
+            if (t0 < T) {
+                int32_t pv[KM], qv[KM];
+                rows_from_chunk<KM>(strips[wave], k_pred, lane, rp[u], pv);
+                rows_from_chunk<KM>(strips[wave], k_ref, lane, rq[u], qv);
+                const int t = t0 + lane;
+                if (t < T) {
+                    const int kp = row_width(k_row, (long long)layer * T + t, k_pred);
+                    score_vals<NW, KM>(pv, kp, qv, k_ref, E, v[0], v[1], v[2], v[3]);
+                }
+            }
+        }
     }
 #pragma unroll
     for (int m = 1; m < 64; m <<= 1)
@@ -156,7 +209,7 @@ __global__ __launch_bounds__(LAYER_THREADS) void score_layer_kernel(
     __syncthreads();
     if (tid < 4) {
         unsigned long long sum = 0;
-        for (int w = 0; w < LAYER_THREADS / 64; ++w) sum += (unsigned long long)part[w][tid];
+        for (int w = 0; w < WAVES; ++w) sum += (unsigned long long)part[w][tid];
         counters[(long long)layer * 4 + tid] = sum;
     }
 }
@@ -165,13 +218,16 @@ template <int NW, int KM>
 static void launch_score_cfg(const int32_t* idx, int k_pred, const int32_t* ref, int k_ref, int L, int T, int E,
                              const int32_t* k_row, unsigned long long* c, hipStream_t stream)
 {
-    if (T <= LAYER_MAX_T) {
-        hipLaunchKernelGGL((score_layer_kernel<NW, KM>), dim3(L), dim3(LAYER_THREADS), 0, stream, idx, k_pred, ref,
-                           k_ref, T, E, k_row, c);
+    // one workgroup per layer while that workgroup's instruction count stays small: it grows with the rows
+    // and with the ids per row the kernel is compiled for
+    if ((long long)T * KM <= (long long)LAYER_MAX_T * 8) {
+        hipLaunchKernelGGL((score_layer_kernel<NW, KM>), dim3(L), dim3(LayerWaves<KM>::value * 64), 0, stream, idx,
+                           k_pred, ref, k_ref, T, E, k_row, c);
         return;
     }
     hipLaunchKernelGGL(score_clear_kernel, dim3((4 * L + 255) / 256), dim3(256), 0, stream, c, 4 * L);
-    dim3 grid((T + SCORE_THREADS - 1) / SCORE_THREADS, L);
+    constexpr int ROWS_PER_WG = SCORE_THREADS * ScoreChunks<KM>::value;
+    dim3 grid((T + ROWS_PER_WG - 1) / ROWS_PER_WG, L);
     hipLaunchKernelGGL((score_kernel<NW, KM>), grid, dim3(SCORE_THREADS), 0, stream, idx, k_pred, ref, k_ref, T, E,
                        k_row, c);
 }
@@ -180,17 +236,18 @@ hipError_t launch_score(const int32_t* idx, int k_pred, const int32_t* ref, int 
                         int L, int T, int E, const int32_t* k_row, long long* counters, hipStream_t stream)
 {
     unsigned long long* c = (unsigned long long*)counters;
-    const bool small_k = k_pred <= 8 && k_ref <= 8;         // the interface allows up to 32 ids per row
-    if (E <= 64) {
-        if (small_k) launch_score_cfg<1, 8>(idx, k_pred, ref, k_ref, L, T, E, k_row, c, stream);
-        else         launch_score_cfg<1, 32>(idx, k_pred, ref, k_ref, L, T, E, k_row, c, stream);
-    } else if (E <= 256) {
-        if (small_k) launch_score_cfg<4, 8>(idx, k_pred, ref, k_ref, L, T, E, k_row, c, stream);
-        else         launch_score_cfg<4, 32>(idx, k_pred, ref, k_ref, L, T, E, k_row, c, stream);
-    } else {
-        if (small_k) launch_score_cfg<16, 8>(idx, k_pred, ref, k_ref, L, T, E, k_row, c, stream);
-        else         launch_score_cfg<16, 32>(idx, k_pred, ref, k_ref, L, T, E, k_row, c, stream);
-    }
+    // ids per row the kernel is compiled for (the interface allows up to 32)
+    const int km = (k_pred <= 8 && k_ref <= 8) ? 8 : ((k_pred <= 16 && k_ref <= 16) ? 16 : 32);
+#define PAEP_SCORE_NW(NWV)                                                                          \
+    do {                                                                                            \
+        if (km == 8)       launch_score_cfg<NWV, 8>(idx, k_pred, ref, k_ref, L, T, E, k_row, c, stream);  \
+        else if (km == 16) launch_score_cfg<NWV, 16>(idx, k_pred, ref, k_ref, L, T, E, k_row, c, stream); \
+        else               launch_score_cfg<NWV, 32>(idx, k_pred, ref, k_ref, L, T, E, k_row, c, stream); \
+    } while (0)
+    if (E <= 64)       PAEP_SCORE_NW(1);
+    else if (E <= 256) PAEP_SCORE_NW(4);
+    else               PAEP_SCORE_NW(16);
+#undef PAEP_SCORE_NW
     return hipGetLastError();
 }
 

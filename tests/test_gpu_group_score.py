@@ -42,6 +42,10 @@ def _check_group(idx, E):
     (8192, 2, 16, 2), (32768, 8, 256, 1), (700, 3, 1000, 2),
     # either side of the single-launch limit of 32768 selections per layer
     (4096, 8, 128, 2), (4097, 8, 128, 2), (32768, 1, 64, 1), (32769, 1, 64, 2), (2000, 16, 1024, 2), (65537, 1, 64, 2),
+    # the single-launch kernel cuts a layer into 2, 4 or 8 independent parts: either side of each switch, ragged
+    # lengths, and a layer too short for its last part to hold anything
+    (4096, 1, 64, 2), (4097, 1, 64, 2), (8192, 1, 64, 2), (8193, 1, 64, 1), (16384, 1, 200, 1), (16385, 1, 256, 2),
+    (2731, 6, 64, 3), (5461, 6, 16, 2), (4099, 7, 100, 2), (2048, 1, 256, 2), (2049, 1, 256, 2), (2049, 1, 257, 1),
 ])
 def test_group_matches_oracle(T, k, E, L):
     g = np.random.default_rng(T * 31 + k * 7 + E)
@@ -56,6 +60,13 @@ def test_group_with_invalid_ids_and_repeats():
     assert int(got.n_invalid.sum()) > 0
     one = np.full((1, 5000, 8), 7, dtype=np.int32)                  # everything lands in one group
     _check_group(one, 128)
+    # the same in the sizes where a layer is cut into parts: -2 and other negative ids among the invalid ones,
+    # valid ids only in the first part (so the later parts own nothing but a stretch of the -1 tail)
+    idx = g.integers(-3, 70, size=(2, 4000, 6)).astype(np.int32)
+    idx[:, 700:] = np.where(idx[:, 700:] % 2 == 0, -2, 64 + idx[:, 700:] % 5)
+    got = _check_group(idx, 64)
+    assert int(got.n_invalid[0]) > 3300 * 6
+    _check_group(np.full((2, 3000, 8), 5, dtype=np.int32), 6)
 
 
 def test_group_is_reproducible():
@@ -73,6 +84,9 @@ def test_group_is_reproducible():
     (5000, 12, 8, 128, 2), (3000, 8, 8, 256, 1), (999, 3, 2, 16, 4), (500, 32, 5, 1000, 1),
     # either side of the single-launch limit of 4096 tokens per layer; more than 8 ids per row
     (4097, 6, 6, 64, 2), (20000, 8, 8, 256, 1), (6000, 20, 9, 700, 1), (300, 9, 32, 64, 2),
+    # nine to sixteen ids per row: one workgroup per layer up to 2048 rows, several beyond; over sixteen: 1024
+    (2048, 16, 16, 64, 2), (2049, 12, 8, 128, 2), (4096, 10, 6, 64, 3), (1024, 20, 9, 64, 2), (1025, 20, 9, 300, 1),
+    (1023, 6, 6, 64, 1), (8191, 2, 2, 16, 2),
 ])
 def test_score_matches_oracle(T, kp, kr, E, L):
     g = np.random.default_rng(T + kp * 3 + E)
