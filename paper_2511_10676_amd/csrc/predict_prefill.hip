@@ -14,8 +14,10 @@
 // the chunk of h goes, after bias, activation and rounding to bf16, straight
 // from the accumulator registers into
 //     z^T[E, tokens] += W2[:, chunk] . h^T[chunk, tokens]
-// without touching LDS; only the W2 fragments are fetched (two 8-byte loads
-// per lane, matching the accumulator's row order).  h and z never reach HBM.
+// without touching LDS; the W2 fragments come from a copy of the chunk's W2
+// slice that was brought into LDS while the chunk's first product ran (two
+// 8-byte reads per lane, matching the accumulator's row order).  h and z never
+// reach HBM.
 // After the last chunk the waves that share a token range add their partial
 // scores through LDS in a fixed order, and one to four lanes per token run the
 // softmax/top-k epilogue.  r may also be split over several workgroups per
@@ -53,9 +55,18 @@ template <int N, class F> __device__ __forceinline__ void static_for(F&& f)
 // ds_read_b128 touch 64 distinct banks.  The swizzle is applied on the global
 // side of the copy (a lane picks which chunk it fetches), because the LDS side
 // of that instruction is fixed to lane * 16 bytes from a wave-uniform base.
-template <int BM_, int BN_, int BK_, int NS_, int WR_, int WT_, int OCC_>
+//   W2L: the chunk's slice of W2 (all experts x BN hidden units) is copied to LDS
+//   a chunk ahead, behind the stages, and the second layer reads its fragments
+//   from there.  Read straight from global memory, every fragment of the second
+//   layer is a load the next matrix instruction waits for (no registers are
+//   free to request them ahead): measured, the second layer then takes 16% of
+//   the loop with 64 experts and 36-39% with 128 and 256.
+template <int BM_, int BN_, int BK_, int NS_, int WR_, int WT_, int OCC_, bool W2L_ = true>
 struct PfCfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, NS = NS_, WR = WR_, WT = WT_, OCC = OCC_;
+    static constexpr bool W2L = W2L_;
+    static constexpr int CW = BN / 8;                       // 16-byte chunks per row of the W2 slice
+    static constexpr int RPIW = 64 / CW;                    // slice rows moved by one copy instruction
     static constexpr int NW = WR * WT, THREADS = 64 * NW;
     static constexpr int WM = BN / WR, WN = BM / WT;        // wave tile: hidden units x tokens
     static constexpr int MI = WM / 32, NI = WN / 32;        // 32 x 32 blocks per wave
@@ -158,6 +169,10 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
 
     const int NK = d / BK;
     const int n_begin = cg * cpg, n_end = n_begin + cpg;     // this work item's chunks of r
+    // The slice's copies are requested after the first barrier of a chunk and must have landed, for every wave,
+    // before a barrier that precedes the chunk's second layer.  A wave's wait before the barrier of tile i lets only
+    // the copies of the NS - 1 youngest tiles stay in flight, so with enough tiles per chunk that holds by itself.
+    const bool w2_sync = NK < NS + 2;
 
     // Global -> LDS requests for the next tile in sequence, one copy instruction
     // ("piece") at a time so that they can be spread between the MFMAs instead
@@ -198,6 +213,28 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     auto issue_tile = [&](int slot) {
         static_for<NP>([&](auto q_c) { issue_piece(slot, q_c); });
         issue_advance();
+    };
+
+    // The W2 slice of a chunk in LDS, behind the stages: row e (expert) holds BN hidden units = CW
+    // chunks of 16 bytes, chunk c in slot c ^ (e % CW) (swizzled on the global side of the copy, like
+    // the tiles).  Rows past E lie outside the buffer resource and arrive as zeros.
+    constexpr int CW = C::CW, RPIW = C::RPIW, W2ROWS = EB32 * 32;
+    constexpr int W2J = C::W2L ? W2ROWS / RPIW / C::NW : 0;     // copy instructions per wave and slice
+    static_assert(!C::W2L || W2J * RPIW * C::NW == W2ROWS, "W2 slice copy split");
+    uint16_t* w2lds = tiles + NS * STAGE_ELEMS;
+    const __amdgpu_buffer_rsrc_t rsrc_w2 =
+        __builtin_amdgcn_make_buffer_rsrc((void*)W2l, 0, (int)((long long)E * r * 2), 0x00020000);
+    auto issue_w2 = [&](int n) {
+        if constexpr (C::W2L) {
+#pragma unroll
+            for (int j = 0; j < W2J; ++j) {
+                const int row0 = (wave * W2J + j) * RPIW;
+                const int e = row0 + lane / CW;
+                const int chunk = (lane % CW) ^ (e % CW);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_w2, (lptr_t)(w2lds + row0 * BN), 16,
+                                                         (int)((uint32_t)(e * r + chunk * 8) * 2u), n * BN * 2, 0, 0);
+            }
+        }
     };
 
     // LDS read offsets (elements) of this lane's first A / B fragment at k-step 0.
@@ -243,7 +280,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     // registers beside the conversion's temporaries), so that their latency runs
     // under the rounding arithmetic; rows past E are clamped for the address and
     // zeroed by a select, which keeps the loads free of branches.
-    constexpr bool EARLY_W2 = (EB32 <= 4) && (MI * NI + EB32 * NI < 12);    // accumulators leave room for the fragments
+    constexpr bool EARLY_W2 = !C::W2L && (EB32 <= 4) && (MI * NI + EB32 * NI < 12);    // accumulators leave room for the fragments
     auto w2_fragment = [&](int eb, int unit0) {
         const int e = eb * 32 + l32;
         const uint16_t* wp = W2l + (long long)(e < E ? e : E - 1) * r + unit0;
@@ -251,6 +288,15 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
         const u32x2 hi = *(const u32x2*)(wp + 8);
         const bool ok = e < E;
         return u32x4{ok ? lo[0] : 0u, ok ? lo[1] : 0u, ok ? hi[0] : 0u, ok ? hi[1] : 0u};
+    };
+    // the same fragment out of the LDS copy of the slice; ubase = first hidden unit of the 16-unit step inside the chunk
+    auto w2_fragment_lds = [&](int eb, int ubase) {
+        const int e = eb * 32 + l32;
+        const char* row = (const char*)w2lds + e * (BN * 2) + 8 * g;
+        const int c0 = ubase >> 3, sw = e % CW;
+        const u32x2 lo = *(const u32x2*)(row + ((c0 ^ sw) << 4));
+        const u32x2 hi = *(const u32x2*)(row + (((c0 + 1) ^ sw) << 4));
+        return u32x4{lo[0], lo[1], hi[0], hi[1]};
     };
     auto second_layer = [&](int n) {
         const bool plain = (act == 0) && (b1 == nullptr);     // uniform: no bias, identity activation
@@ -296,13 +342,29 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
                         hb[ni] = __builtin_bit_cast(bf16x8, pk);
                     }
                 }
+                if constexpr (C::W2L) {
+                    // fragments from LDS, the next one requested before the current one is multiplied
+                    const int ubase = wr * WM + mi * 32 + 16 * s;
+                    u32x4 cur = w2_fragment_lds(0, ubase);
 #pragma unroll
-                for (int eb = 0; eb < EB32; ++eb) {
-                    if constexpr (!EARLY_W2) wv[eb] = w2_fragment(eb, unit0);
-                    const bf16x8 wa = __builtin_bit_cast(bf16x8, wv[eb]);
+                    for (int eb = 0; eb < EB32; ++eb) {
+                        u32x4 nxt = cur;
+                        if (eb + 1 < EB32) nxt = w2_fragment_lds(eb + 1, ubase);
+                        const bf16x8 wa = __builtin_bit_cast(bf16x8, cur);
 #pragma unroll
-                    for (int ni = 0; ni < NI; ++ni)
-                        acc2[eb][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, hb[ni], acc2[eb][ni], 0, 0, 0);
+                        for (int ni = 0; ni < NI; ++ni)
+                            acc2[eb][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, hb[ni], acc2[eb][ni], 0, 0, 0);
+                        cur = nxt;
+                    }
+                } else {
+#pragma unroll
+                    for (int eb = 0; eb < EB32; ++eb) {
+                        if constexpr (!EARLY_W2) wv[eb] = w2_fragment(eb, unit0);
+                        const bf16x8 wa = __builtin_bit_cast(bf16x8, wv[eb]);
+#pragma unroll
+                        for (int ni = 0; ni < NI; ++ni)
+                            acc2[eb][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, hb[ni], acc2[eb][ni], 0, 0, 0);
+                    }
                 }
                 __builtin_amdgcn_sched_barrier(0);          // keep the W2 fetches of later steps from piling up in registers
             }
@@ -333,6 +395,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     // PRO tiles requested up front; tile 0 has landed for everyone after the barrier.
     // (With DEFER the coordinates stay on the last requested tile: the main loop's
     // first deferred half-copy repeats that tile's second half, then advances.)
+    issue_w2(n_begin);                                            // oldest copies in flight: landed once tile 0 has
 #pragma unroll
     for (int p = 0; p < PRO; ++p) {
         static_for<NP>([&](auto q_c) { issue_piece(p, q_c); });
@@ -386,6 +449,9 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
                 } else {
                     __builtin_amdgcn_s_waitcnt(WAIT_NEXT);
                     wg_barrier();
+                    // Every wave is past the previous chunk's second layer here, so the slice in LDS may
+                    // be replaced by this chunk's; it is read at the end of the chunk, NK - 1 tiles later.
+                    if (C::W2L && kt == 0 && n > n_begin) issue_w2(n);
                     if constexpr (!DEFER) issue_tile(free_slot);
                     // With many experts the score accumulators leave no room to carry the next
                     // tile's first fragments across the second layer: fetch them after it instead.
@@ -405,6 +471,11 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
             });
             free_slot = LAG ? slot : nslot;
             slot = nslot;
+        }
+        if (C::W2L && w2_sync) {
+            // few tiles per chunk: the slice's copies may still be among the youngest in flight
+            __builtin_amdgcn_s_waitcnt(PAEP_VMCNT(0));
+            wg_barrier();
         }
         second_layer(n);
         if constexpr (LATE_FRAGS) {
@@ -558,26 +629,30 @@ __global__ void prefill_clear_tickets(int* tickets, int n)
     if (i < n) tickets[i] = 0;
 }
 
-// Configurations.  Big: 256 x 256 tiles, 8 waves, one workgroup per CU -- the
-// fewest bytes per flop through the CU's vector memory path, for E <= 64; five
-// stages of 32 KB fill the CU's 160 KB of LDS (three tiles of latency cover).
-// BigDeep: the same tile in two 64-wide stages, measured +3% at d = 4096 and
-// no better at d = 2048.
-// BigWide: the 256 x 256 tile in two 64-wide stages with the 8 waves side by
-// side along tokens (256 units x 32 tokens each): 128 + 64 accumulators per
-// lane for 64 < E <= 128, a third fewer bytes copied per flop than Mid and half
-// as many barriers; measured +3% over Mid on the Qwen shape.
-// Mid: 256 tokens x 128 hidden units in 64-wide k tiles for 64 < E <= 128, waves
-// 2 x 4 (64 units x 64 tokens each: one LDS fragment read per matrix
-// instruction, 128 score accumulators per lane).  MidWide: the same tile with
-// the 8 waves side by side along tokens, which halves the score accumulators
-// per lane (E up to 256) at 1.25 fragment reads per matrix instruction.
-// Small: 128 x 128, 4 waves, any r that is a multiple of 128 and short inputs.
-typedef PfCfg<256, 256, 32, 5, 2, 4, 1> CfgBig;
+// Configurations (all 8 waves and one workgroup per CU except Small).  The 160 KB of
+// LDS hold the stages and, behind them, the chunk's W2 slice (E rounded up to 32 rows x
+// BN hidden units x 2 bytes):
+//   Big       256 x 256 tile, waves 2 x 4 (128 units x 64 tokens each: 0.75 LDS fragment reads per
+//             matrix instruction, the fewest bytes per flop through the CU's vector memory path),
+//             E <= 64; four 32-wide stages of 32 KB + 32 KB slice.
+//   BigDeep   the same tile in two 64-wide stages (64 KB each) + 32 KB slice: half as many barriers
+//             per flop, measured +3% at d = 4096 and no better at d = 2048.
+//   BigWide   the 256 x 256 tile with the 8 waves side by side along tokens (256 units x 32 tokens
+//             each: 128 + 64 accumulators per lane) for 64 < E <= 128; three 32-wide stages + 64 KB
+//             slice.  Measured on the Qwen3-30B-A3B shape: 934 TFLOP/s against 791 for Mid.
+//   Mid       256 tokens x 128 hidden units, waves 2 x 4 (64 units x 64 tokens each, 128 score
+//             accumulators per lane), 64 < E <= 128 when r is not a multiple of 256; five 32-wide
+//             stages of 24 KB + 32 KB slice.
+//   MidWide   the same tile with the waves side by side along tokens, which halves the score
+//             accumulators per lane (E up to 256) at 1.25 fragment reads per matrix instruction;
+//             four stages of 24 KB + 64 KB slice.
+//   Small     128 x 128, 4 waves, two workgroups per CU (4 x 16 KB + 16 KB slice each): short inputs
+//             and any r that is a multiple of 128.  SmallWide: the same for E > 64 (64 KB slice).
+typedef PfCfg<256, 256, 32, 4, 2, 4, 1> CfgBig;
 typedef PfCfg<256, 256, 64, 2, 2, 4, 1> CfgBigDeep;      // long rows (d >= 4096): half as many barriers per flop
-typedef PfCfg<256, 128, 64, 3, 2, 4, 1> CfgMid;
-typedef PfCfg<256, 256, 64, 2, 1, 8, 1> CfgBigWide;      // 64 < E <= 128, r a multiple of 256
-typedef PfCfg<256, 128, 64, 3, 1, 8, 1> CfgMidWide;
+typedef PfCfg<256, 128, 32, 5, 2, 4, 1> CfgMid;
+typedef PfCfg<256, 256, 32, 3, 1, 8, 1> CfgBigWide;      // 64 < E <= 128, r a multiple of 256
+typedef PfCfg<256, 128, 32, 4, 1, 8, 1> CfgMidWide;
 typedef PfCfg<128, 128, 32, 4, 2, 2, 2> CfgSmall;
 typedef PfCfg<128, 128, 32, 4, 1, 4, 1> CfgSmallWide;
 
@@ -586,7 +661,9 @@ static size_t cfg_lds_bytes(int E)
 {
     // score tile of the epilogue, then E activation counters
     const size_t z = sizeof(float) * (size_t)PfZRows<C, EB32>::value * (size_t)(E + 1) + sizeof(int32_t) * (size_t)E;
-    return z > (size_t)C::TILE_BYTES ? z : (size_t)C::TILE_BYTES;
+    // main loop: the stages, then the W2 slice (32 * EB32 rows of BN hidden units)
+    const size_t loop = (size_t)C::TILE_BYTES + (C::W2L ? (size_t)EB32 * 32 * C::BN * 2 : 0);
+    return z > loop ? z : loop;
 }
 
 bool prefill_supported(const PredictArgs& a)
@@ -669,7 +746,7 @@ static int pick_cfg(const PredictArgs& a)
 {
     const bool large = enough_large_tiles(a);
     if (a.E <= 64) return (large && a.r % 256 == 0) ? 2 : 0;
-    if (!(large && a.d % 64 == 0)) return 1;                  // the configurations below walk d in steps of 64
+    if (!large) return 1;
     return (a.E <= 128 && a.r % 256 == 0) ? 4 : 3;
 }
 

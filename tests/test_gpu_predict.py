@@ -174,7 +174,8 @@ def test_empty_call():
     (64, 6, 768, 64, 4, 8229), (64, 6, 1024, 64, 16, 8229), (128, 8, 640, 64, 9, 8229), (16, 2, 1280, 32, 1, 33000),
     # 64 < E <= 128 with r a multiple of 256: the 256 x 256 tile with the waves side by side
     (128, 8, 512, 64, 4, 8229), (100, 8, 256, 128, 4, 8229),
-    # more than 64 experts with d not a multiple of 64: the 64-wide-tile configurations must not be chosen
+    # more than 64 experts with d = 96 and d = 32: three tiles and one tile per chunk of r, so the W2 slice in
+    # LDS has to be waited for explicitly before each second product
     (128, 8, 256, 96, 4, 8229), (200, 8, 256, 32, 4, 8229),
 ])
 def test_prefill_large_tile_configs_with_ragged_tail(E, k, r, d, L, T):
