@@ -241,6 +241,83 @@ __device__ __forceinline__ void wave_softmax_topk(const float (&z)[NV], int E, i
     }
 }
 
+// The same outputs for a row of at most 128 scores (NV <= 2 per lane), by rank counting:
+// every lane learns how many of the row's keys beat its own by walking the 64 lanes' keys
+// through scalar registers (v_readlane: no LDS round trip, no dependent chain of shuffles).
+// Keys are distinct (the expert id is part of the key), so the ranks are a permutation and the
+// lane whose key has rank j < k writes output j.  Selection and order are exactly those of
+// wave_softmax_topk; the softmax normaliser is the same butterfly sum.
+template <int NV>
+__device__ __forceinline__ void wave_softmax_topk_rank(const float (&z)[NV], int E, int k, int lane,
+                                                       int32_t* idx_row, float* probs_row, const EpilogueOut& o)
+{
+    static_assert(NV <= 2, "rank counting is for short rows");
+    uint32_t khi[NV], klo[NV];
+    int rank[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int e = lane + 64 * v;
+        const uint64_t key = (e < E) ? make_key(z[v], e) : 0ull;
+        khi[v] = (uint32_t)(key >> 32);
+        klo[v] = (uint32_t)key;
+        rank[v] = 0;
+    }
+    for (int j = 0; j < 64; ++j) {                             // uniform: lane j's keys, broadcast
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const uint32_t ohi = (uint32_t)__builtin_amdgcn_readlane((int)khi[u], j);
+            const uint32_t olo = (uint32_t)__builtin_amdgcn_readlane((int)klo[u], j);
+#pragma unroll
+            for (int v = 0; v < NV; ++v) rank[v] += (ohi > khi[v] || (ohi == khi[v] && olo > klo[v])) ? 1 : 0;
+        }
+    }
+    // score of the key with a given rank, for every lane (rank < number of valid keys)
+    auto score_of_rank = [&](int want) {
+        float found = 0.0f;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const unsigned long long who = __ballot(rank[v] == want && lane + 64 * v < E);
+            if (who) found = __uint_as_float((uint32_t)__builtin_amdgcn_readlane(
+                         (int)__float_as_uint(z[v]), (int)__builtin_ctzll(who)));
+        }
+        return found + 0.0f;
+    };
+    // row maximum as the other routine takes it: the score of the best key (NaNs order last, -0 reads as +0)
+    const float m = key_score(((uint64_t)orderable(score_of_rank(0)) << 32));
+    float s = 0.0f;
+    if (o.prob_mode == 0) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int e = lane + 64 * v;
+            if (e < E && z[v] == z[v]) s += __expf(z[v] - m);
+        }
+    } else if (o.prob_mode == 1) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v)
+            if (lane + 64 * v < E && rank[v] < k) s += __expf(key_score(((uint64_t)khi[v] << 32)) - m);
+    }
+    if (o.prob_mode != 2) {
+#pragma unroll
+        for (int mask = 1; mask < 64; mask <<= 1) s += __shfl_xor(s, mask, 64);
+    }
+    if (o.margin_row) {
+        float mg = __builtin_inff();
+        if (k < E) mg = key_score(((uint64_t)orderable(score_of_rank(k - 1)) << 32)) -
+                        key_score(((uint64_t)orderable(score_of_rank(k)) << 32));
+        if (lane == 0) *o.margin_row = mg;
+    }
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int e = lane + 64 * v;
+        if (e < E && rank[v] < k) {
+            const float sc = key_score(((uint64_t)khi[v] << 32));
+            idx_row[rank[v]] = e;
+            probs_row[rank[v]] = (o.prob_mode == 2) ? sigmoidf_(sc) : __expf(sc - m) / s;
+            if (o.counts_row) atomicAdd(&o.counts_row[e], 1);
+        }
+    }
+}
+
 // Same, for kernels that only accept lists of up to 16 (keeps their register budget small):
 // k <= 16, and k <= 15 when the margin is wanted and k < E.
 template <int G>

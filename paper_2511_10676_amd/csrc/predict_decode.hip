@@ -250,8 +250,9 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(
 
 // One wave per token row: lane l owns experts l, l+64, ...  The slice partials
 // are summed in ascending slice order, eight loads in flight at a time.
-static constexpr int FIN_NV = 8;                          // experts per lane: E <= 512
+static constexpr int FIN_NV = 8;                          // experts per lane at most: E <= 512
 
+template <int NV>                                         // experts per lane: E <= 64 * NV
 __global__ __launch_bounds__(DEC_THREADS) void decode_finalize_kernel(
     int T, int E, int k, int S, int rows_total, const float* __restrict__ partial,
     const uint16_t* __restrict__ b2, int32_t* __restrict__ idx, float* __restrict__ probs,
@@ -263,9 +264,9 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_finalize_kernel(
     const int layer = row / T, t = row - layer * T;
     const long long sstride = (long long)T * E;
     const float* src = partial + ((long long)layer * S * T + t) * E;
-    float z[FIN_NV];
+    float z[NV];
 #pragma unroll
-    for (int v = 0; v < FIN_NV; ++v) {
+    for (int v = 0; v < NV; ++v) {
         const int e = lane + 64 * v;
         float acc = 0.0f;
         if (e < E) {
@@ -291,7 +292,8 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_finalize_kernel(
         z[v] = acc;
     }
     const EpilogueOut eo{prob_mode, margin ? margin + row : nullptr, counts ? counts + (long long)layer * E : nullptr};
-    wave_softmax_topk<FIN_NV>(z, E, k, lane, idx + (long long)row * k, probs + (long long)row * k, eo);
+    if constexpr (NV <= 2) wave_softmax_topk_rank<NV>(z, E, k, lane, idx + (long long)row * k, probs + (long long)row * k, eo);
+    else                   wave_softmax_topk<NV>(z, E, k, lane, idx + (long long)row * k, probs + (long long)row * k, eo);
 }
 
 bool decode_supported(const PredictArgs& a)
@@ -330,9 +332,15 @@ hipError_t launch_predict_decode(const PredictArgs& a)
     if (err != hipSuccess) return err;
     const int rows = a.L * a.T;
     const int rows_per_wg = DEC_THREADS / 64;
-    hipLaunchKernelGGL(decode_finalize_kernel, dim3((rows + rows_per_wg - 1) / rows_per_wg), dim3(DEC_THREADS), 0,
-                       a.stream, a.T, a.E, a.k, S, rows, partial, (const uint16_t*)a.b2, a.idx, a.probs, a.logits,
-                       a.counts, a.prob_mode, a.margin);
+#define PAEP_LAUNCH_FIN(NVV)                                                                                \
+    hipLaunchKernelGGL(decode_finalize_kernel<NVV>, dim3((rows + rows_per_wg - 1) / rows_per_wg), dim3(DEC_THREADS), \
+                       0, a.stream, a.T, a.E, a.k, S, rows, partial, (const uint16_t*)a.b2, a.idx, a.probs,          \
+                       a.logits, a.counts, a.prob_mode, a.margin)
+    if (a.E <= 64)       PAEP_LAUNCH_FIN(1);
+    else if (a.E <= 128) PAEP_LAUNCH_FIN(2);
+    else if (a.E <= 256) PAEP_LAUNCH_FIN(4);
+    else                 PAEP_LAUNCH_FIN(8);
+#undef PAEP_LAUNCH_FIN
     return hipGetLastError();
 }
 
