@@ -91,7 +91,8 @@ struct PfZRows {
 // EB32: 32-expert blocks (E <= 32 * EB32).
 template <class C, int EB32>
 __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
-    int T, int d, int r, int E, int k, int act, int tiles_per_layer, int total_wgs, int groups, int cpg,
+    int T, int d, int r, int E, int k, int act, int tiles_per_layer, int main_wgs, int main_groups, int tail_wgs,
+    int tail_groups, int split_tile0, int nchunks,
     long long xs_, long long w1s, long long w2s,
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ W1, const uint16_t* __restrict__ W2,
     const uint16_t* __restrict__ b1, const uint16_t* __restrict__ b2,
@@ -114,14 +115,23 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     // of one layer: every x tile is shared by `groups` workgroups and every W1
     // chunk by several token tiles through that XCD's L2, instead of each
     // workgroup pulling its own x tile from far memory once per chunk.
+    // The grid has two parts: `main_wgs` workgroups that run the first tiles with `main_groups`
+    // workgroups per tile, then `tail_wgs` that run the remaining tiles with `tail_groups` each (the
+    // tiles that would otherwise form a last, partly filled round of whole-tile workgroups are cut
+    // finer so that every CU stays busy to the end).  Each part is remapped by itself.
     int wg = blockIdx.x;
+    const bool in_tail = wg >= main_wgs;
     {
-        const int per = total_wgs / 8, rem = total_wgs % 8;
+        const int part_wgs = in_tail ? tail_wgs : main_wgs;
+        if (in_tail) wg -= main_wgs;
+        const int per = part_wgs / 8, rem = part_wgs % 8;
         const int xcd = wg % 8, slot = wg / 8;
         wg = xcd * per + (xcd < rem ? xcd : rem) + slot;
     }
+    const int groups = in_tail ? tail_groups : main_groups;
+    const int cpg = nchunks / groups;
     const int cg = wg % groups;
-    const int tile_id = wg / groups;                      // layer * tiles_per_layer + token tile
+    const int tile_id = (in_tail ? main_wgs / main_groups : 0) + wg / groups;   // layer * tiles_per_layer + token tile
     const int layer = tile_id / tiles_per_layer;
     const int t0 = (tile_id - layer * tiles_per_layer) * BM;
 
@@ -572,7 +582,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     // workspace as zpart[tile][group][token][expert]; the workgroup that arrives
     // last (ticket counter, release/acquire fences) adds the groups in ascending
     // order -- a fixed order, whoever is last -- and finishes the rows.
-    float* zmine = zpart + ((long long)tile_id * groups + cg) * BM * E;
+    float* zmine = zpart + ((long long)(tile_id - split_tile0) * groups + cg) * BM * E;
 #pragma unroll 1
     for (int zp = 0; zp < BM / ZROWS; ++zp) {
         regs_to_lds(zp);
@@ -590,7 +600,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     int* flag = (int*)smem_raw;
     if (tid == 0) {
         __threadfence();
-        const int ticket = atomicAdd(&tickets[tile_id], 1);
+        const int ticket = atomicAdd(&tickets[tile_id - split_tile0], 1);
         if (ticket == groups - 1) __threadfence();
         *flag = ticket;
     }
@@ -598,7 +608,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC) void prefill_kernel(
     const bool last = (*flag == groups - 1);
     __syncthreads();
     if (!last) return;
-    const float* zall = zpart + (long long)tile_id * groups * BM * E;
+    const float* zall = zpart + (long long)(tile_id - split_tile0) * groups * BM * E;
 #pragma unroll 1
     for (int zp = 0; zp < BM / ZROWS; ++zp) {
         if (t0 + zp * ZROWS >= T) break;                      // no tokens left in this tile (uniform)
@@ -700,37 +710,82 @@ static int prefill_groups(const PredictArgs& a)
     return ((long long)a.d * C::BM * 2 >= (2ll << 20)) ? 2 : 1;
 }
 
+// How a launch is laid out: `main_tiles` token tiles with `main_groups` workgroups each, then
+// `tail_tiles` with `tail_groups` each.  With whole-tile workgroups (main_groups = 1) the tiles beyond the
+// last full round of 256 would keep a fraction of the CUs busy for a whole tile's duration; where it pays
+// they are cut along r into pieces short enough to fill every CU evenly, at the price of the score-tile
+// exchange (measured, 2048 x 2048 layers of 16 tiles: 20 layers 842 -> 985 TFLOP/s, 24 layers 934 -> 1015;
+// with 26 layers the tail of 160 tiles is too long for any cut to win and stays whole).
+struct PfLayout {
+    int main_tiles, main_groups, tail_tiles, tail_groups;
+    int split_tile0, split_tiles, split_groups;              // the tiles that go through the workspace
+};
+template <class C>
+static PfLayout cfg_layout(const PredictArgs& a)
+{
+    const int NC = a.r / C::BN;
+    const int tiles = ((a.T + C::BM - 1) / C::BM) * a.L;
+    PfLayout f{tiles, prefill_groups<C>(a), 0, 1, 0, 0, 1};
+    if (f.main_groups > 1) {
+        f.split_tiles = tiles;
+        f.split_groups = f.main_groups;
+        return f;
+    }
+    constexpr int CUS = 256;
+    const int tail = tiles % CUS;
+    if (tiles < CUS || tail == 0) return f;
+    // Time of the tail in units of one whole-tile workgroup on a full chip, from measurements on 2048 x 2048
+    // layers: uncut, the tail's workgroups run faster than on a full chip (the clock rises when CUs idle:
+    // 0.62 for 64 tiles, 0.76 for 128, 0.92 for 160); cut g ways they take 1/g plus about 0.08 each (pipeline
+    // fill, the score-tile exchange, and the XCD's workgroups no longer walking the same chunk of W1).
+    int best = 1;
+    double best_t = 0.55 + 0.40 * tail / CUS;
+    for (int g = 2; g <= 8 && g <= NC; g *= 2) {
+        if (NC % g != 0) continue;
+        const double t = (double)((tail * g + CUS - 1) / CUS) * (1.0 / g + 0.08);
+        if (t < best_t - 0.05) { best_t = t; best = g; }
+    }
+    if (best == 1) return f;
+    f.main_tiles = tiles - tail;
+    f.tail_tiles = tail;
+    f.tail_groups = best;
+    f.split_tile0 = f.main_tiles;
+    f.split_tiles = tail;
+    f.split_groups = best;
+    return f;
+}
+
 template <class C>
 static size_t cfg_workspace_bytes(const PredictArgs& a)
 {
-    const int groups = prefill_groups<C>(a);
-    if (groups == 1) return 0;
-    const size_t tiles = (size_t)((a.T + C::BM - 1) / C::BM) * a.L;
-    return tiles * groups * C::BM * a.E * sizeof(float) + ((tiles * sizeof(int) + 15) / 16) * 16;
+    const PfLayout f = cfg_layout<C>(a);
+    if (f.split_tiles == 0) return 0;
+    return (size_t)f.split_tiles * f.split_groups * C::BM * a.E * sizeof(float) +
+           (((size_t)f.split_tiles * sizeof(int) + 15) / 16) * 16;
 }
 
 template <class C, int EB32>
 static hipError_t launch_cfg(const PredictArgs& a)
 {
     const int tiles = (a.T + C::BM - 1) / C::BM;
-    const int groups = prefill_groups<C>(a);
-    const int cpg = a.r / C::BN / groups;
-    const int total = tiles * a.L * groups;
+    const PfLayout f = cfg_layout<C>(a);
+    const int main_wgs = f.main_tiles * f.main_groups, tail_wgs = f.tail_tiles * f.tail_groups;
     const size_t lds = cfg_lds_bytes<C, EB32>(a.E);
     float* zpart = nullptr;
     int* tickets = nullptr;
-    if (groups > 1) {
+    if (f.split_tiles > 0) {
         zpart = (float*)a.workspace;
-        tickets = (int*)((char*)a.workspace + (size_t)tiles * a.L * groups * C::BM * a.E * sizeof(float));
-        const int nt = tiles * a.L;
-        hipLaunchKernelGGL(prefill_clear_tickets, dim3((nt + 255) / 256), dim3(256), 0, a.stream, tickets, nt);
+        tickets = (int*)((char*)a.workspace + (size_t)f.split_tiles * f.split_groups * C::BM * a.E * sizeof(float));
+        hipLaunchKernelGGL(prefill_clear_tickets, dim3((f.split_tiles + 255) / 256), dim3(256), 0, a.stream, tickets,
+                           f.split_tiles);
     }
     auto kern = prefill_kernel<C, EB32>;
     static LdsLimit limit;
     hipError_t err = ensure_lds_limit(limit, (const void*)kern, lds);
     if (err != hipSuccess) return err;
-    hipLaunchKernelGGL(kern, dim3(total), dim3(C::THREADS), lds, a.stream, a.T, a.d, a.r, a.E, a.k, a.act, tiles,
-                       total, groups, cpg, a.x_stride, a.w1_stride, a.w2_stride, (const uint16_t*)a.x,
+    hipLaunchKernelGGL(kern, dim3(main_wgs + tail_wgs), dim3(C::THREADS), lds, a.stream, a.T, a.d, a.r, a.E, a.k, a.act,
+                       tiles, main_wgs, f.main_groups, tail_wgs, f.tail_groups, f.split_tile0, a.r / C::BN,
+                       a.x_stride, a.w1_stride, a.w2_stride, (const uint16_t*)a.x,
                        (const uint16_t*)a.W1, (const uint16_t*)a.W2, (const uint16_t*)a.b1,
                        (const uint16_t*)a.b2, a.idx, a.probs, a.logits, zpart, tickets, a.counts, a.prob_mode,
                        a.margin);
@@ -753,8 +808,9 @@ static int pick_cfg(const PredictArgs& a)
 template <class C>
 static void cfg_plan(const PredictArgs& a, int* groups, int* cpg)
 {
-    *groups = prefill_groups<C>(a);
-    *cpg = a.r / C::BN / *groups;
+    const PfLayout f = cfg_layout<C>(a);
+    *groups = f.main_groups;
+    *cpg = a.r / C::BN / f.main_groups;
 }
 
 void prefill_plan(const PredictArgs& a, int* cfg, int* groups, int* chunks_per_group)

@@ -91,9 +91,14 @@ def test_path_resolution_by_shape():
     assert B.resolve_path(_desc(T=4096, dtype=B.BF16, d=72, r=40, E=13, k=5)) == "simple"
     assert B.resolve_path(_desc(T=4096, dtype=B.BF16, d=2048, r=4096, E=256, k=8)) == "prefill"
     assert B.resolve_path(_desc(k=0)) == "invalid"
-    # with many tiles prefill needs no workspace unless the token tile is large enough (d >= 4096) for r to
-    # be split over two co-scheduled workgroups: then two score tiles of 256 x E fp32 per tile plus a ticket
+    # with a whole number of rounds of 256 token tiles prefill needs no workspace (32 layers x 16 tiles), nor
+    # when the tiles beyond the last full round are too many for cutting them to pay (26 x 16 = 256 + 160) ...
+    assert B.predict_workspace_bytes(_desc(T=4096, **dict(ds, L=32))) == 0
     assert B.predict_workspace_bytes(_desc(T=4096, **ds)) == 0
+    # ... otherwise those tiles (20 x 16 = 256 + 64) are cut along r into 4 pieces each, whose score tiles of
+    # 256 x E fp32 meet in the workspace, plus a ticket per tile ...
+    assert B.predict_workspace_bytes(_desc(T=4096, **dict(ds, L=20))) == 64 * 4 * 256 * 64 * 4 + 64 * 4
+    # ... and with long rows (d >= 4096) r is split over two co-scheduled workgroups for every tile
     phi = dict(dtype=B.BF16, d=4096, r=1024, E=16, k=2, L=32)
     tiles = (8192 // 256) * 32
     assert B.predict_workspace_bytes(_desc(T=8192, **phi)) == tiles * 2 * 256 * 16 * 4 + tiles * 4

@@ -193,6 +193,11 @@ def test_prefill_large_tile_configs_with_ragged_tail(E, k, r, d, L, T):
     (128, 8, 1024, 64, 8, 8229, "256x256 wide", 1, 4),
     (256, 8, 512, 64, 8, 8229, "256x128", 1, 4),
     (200, 12, 640, 128, 8, 8229, "256x128", 1, 5),
+    # 9 layers x 33 tiles = 256 + 41: the 41 tiles beyond the full round are cut along r into four pieces each
+    # that meet in the workspace, the other 256 are not (same kernel, two parts of one grid)
+    (64, 6, 1024, 64, 9, 8229, "256x256", 1, 4),
+    (128, 8, 1024, 64, 9, 8229, "256x256 wide", 1, 4),
+    (256, 8, 512, 64, 9, 8229, "256x128", 1, 4),
     # ... and with long rows (d = 4096) r split over two workgroups per tile, again at >= 256 tiles:
     # score tiles through the workspace, last arriver adds them (release/acquire through one thread's fences)
     (64, 6, 512, 4096, 8, 8300, "256x256", 2, 1),
