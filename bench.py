@@ -20,7 +20,7 @@ again with the over-provisioned prediction width the paper evaluates
 (section 5.2), all on the same weight banks.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--T tokens] [--k-pred K'] [--no-cpu]
-                    [--only] [--pipeline] [--copy-probe-mib N]
+                    [--only] [--counted] [--pipeline] [--copy-probe-mib N]
 """
 import argparse
 import json
@@ -44,8 +44,12 @@ MALL_BYTES = 256 << 20
 # once a kernel's code changes, the figure no longer describes it and the
 # report says null.
 TRAFFIC_BYTES = {
-    ("prefill", "aef598af1b332dad"): {("deepseek_v2_lite", 4096): 3.87e+09},
-    ("decode", "18bfb2d8d07fe899"): {("deepseek_v2_lite", 1): 2.382e+08, ("deepseek_v2_lite", 64): 3.241e+08},
+    ("prefill", "be865277bf0be11a"): {("deepseek_v2_lite", 4096): 3.891e+09,
+                                      ("qwen3_30b_a3b", 8192): 1.457e+10,
+                                      ("phi_mini_moe", 8192): 4.91e+09,
+                                      ("stress", 32768): 2.41e+11},
+    ("decode", "1271cebe783c937f"): {("deepseek_v2_lite", 1): 2.395e+08,
+                                     ("deepseek_v2_lite", 64): 2.633e+08},
 }
 
 
@@ -114,7 +118,7 @@ class Banks:
 class Runner:
     """Device buffers for one workload at one token count, and the step."""
 
-    def __init__(self, w, T, banks, k_pred=None, pipelined=False):
+    def __init__(self, w, T, banks, k_pred=None, pipelined=False, counted=False):
         import numpy as np
         import torch
         from paper_2511_10676_amd import binding as B
@@ -155,8 +159,11 @@ class Runner:
         self.ready = [torch.cuda.Event() for _ in range(nset)]
         self.done = [torch.cuda.Event() for _ in range(nset)]
         # every call of a step is checked and marshalled once; the timed loop only enqueues
+        # --counted: the predict call also accumulates the activation counts of its selections (paep_predict_counted)
+        self.counts = torch.zeros((L, w.E), dtype=torch.int32, device=dev) if counted else None
         self.p_predict = [[B.prepare_predict(self.x, self.W1[b], self.W2[b], kp, b2=self.b2, out=self.outs[k],
-                                             workspace=self.ws) for k in range(nset)] for b in range(n_banks)]
+                                             workspace=self.ws, counts=self.counts) for k in range(nset)]
+                          for b in range(n_banks)]
         self.p_group = [B.prepare_group_by_expert(self.outs[k].idx, w.E, out=self.grps[k], workspace=self.gwss[k])
                         for k in range(nset)]
         self.p_score = [B.prepare_score(self.outs[k].idx, self.ref, w.E, out=self.cnts[k]) for k in range(nset)]
@@ -327,6 +334,9 @@ def main():
                          "at prefill sizes, slower at decode sizes, and the predict kernel is then timed under "
                          "contention)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--counted", action="store_true",
+                    help="predict through paep_predict_counted: activation counts accumulated in the predictor's "
+                         "epilogue (for pricing that option; the step still runs group_by_expert)")
     ap.add_argument("--only", action="store_true",
                     help="time only the chosen token count (skip the workload's other token counts and the "
                          "over-provisioned width)")
@@ -357,7 +367,7 @@ def main():
     from paper_2511_10676_amd import binding as B
     ceilings = device_ceilings(torch, B)
     banks = Banks(w)
-    run = Runner(w, T, banks, k_pred=args.k_pred or None, pipelined=args.pipeline)
+    run = Runner(w, T, banks, k_pred=args.k_pred or None, pipelined=args.pipeline, counted=args.counted)
     main_rep = run.report(args.steps, args.warmup)
     line = {
         "metric": "predicted tokens*layers per second",
@@ -368,7 +378,7 @@ def main():
         "config": {"workload": f"{w.name}-shaped: L={w.L} d={w.d} r={w.r} E={w.E} k={w.k}, T={T} tokens/layer "
                                f"({main_rep['path']} path, {main_rep['launch']}), step = predict + group_by_expert "
                                f"+ score, all layers",
-                   "k_pred": run.k_pred,
+                   "k_pred": run.k_pred, "counted_predict": bool(args.counted),
                    "streams": ("2: group_by_expert + score of step i run beside predict of step i+1"
                                if run.pipelined else "1"),
                    "weight_banks": main_rep["weight_banks"],
