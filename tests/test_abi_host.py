@@ -121,12 +121,16 @@ def test_group_rejects_bad_arguments():
     assert _group(T=1 << 29, k=2) == E_SHAPE
     assert _group(outs=(None,) + (FAKE,) * 5) == E_NULL
     assert _group(T=4, idx=None) == E_NULL
-    # more than 32768 selections per layer: three launches that meet in a workspace
+    # more than 32768 selections per layer: the parts' counts meet in a workspace, (parts + 1) rows of E + 1
     assert _group(T=8192, k=8, E=256, ws=None) == E_WS
     assert _group(T=8192, k=8, E=256, ws_bytes=16) == E_WS
     assert _group(T=8192, k=8, E=256, ws=ODD) == E_WS
-    assert B.group_workspace_bytes(1, 8192, 8, 256) == 4 * 64 * 257
-    assert B.group_workspace_bytes(3, 8192, 8, 256) == 3 * 4 * 64 * 257
+    assert B.group_workspace_bytes(1, 8192, 8, 256) == 4 * 9 * 257
+    assert B.group_workspace_bytes(3, 8192, 8, 256) == 3 * 4 * 9 * 257
+    assert B.group_workspace_bytes(1, 32768, 8, 256) == 4 * 33 * 257
+    assert B.group_workspace_bytes(1, 70000, 8, 64) == 4 * 36 * 65              # 35 parts of 16384
+    assert B.group_workspace_bytes(1, 262200, 8, 64) == 4 * 66 * 65             # 65 parts of 32768
+    assert B.group_workspace_bytes(2, 66000, 16, 1024) == 2 * 4 * 66 * 1025     # 1024 experts: parts of 16384 at most
     # shorter layers run in one launch out of LDS and need none (a NULL workspace is then accepted:
     # checked with real buffers in the GPU tests, since every valid call launches)
     assert B.group_workspace_bytes(1, 4096, 8, 256) == 0

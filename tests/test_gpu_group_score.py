@@ -53,6 +53,26 @@ def test_group_matches_oracle(T, k, E, L):
     _check_group(idx, E)
 
 
+@pytest.mark.parametrize("T,k,E,L,lo", [
+    # layers beyond 32768 selections: parts of 8192 positions counted by a launch of their own
+    (8192, 8, 128, 3, 0), (8193, 8, 128, 2, 0), (32768, 8, 256, 2, 0), (4097, 8, 1024, 2, -2), (40000, 4, 1000, 1, 0),
+    (32769, 1, 7, 2, -1), (9000, 10, 64, 2, 0),
+    # more than 64 parts of 8192: longer parts (35 of 16384; 63 and 64 of 32768)
+    (70000, 8, 64, 1, 0), (258000, 8, 256, 1, 0), (262144, 8, 128, 1, -1),
+    # more than 64 parts of the longest kind LDS allows: the columns get a launch of their own
+    (262200, 8, 64, 2, -1), (66000, 16, 1024, 1, 0), (300000, 9, 300, 1, -3),
+])
+def test_group_long_layers(T, k, E, L, lo):
+    g = np.random.default_rng(T + k + E)
+    hi = E + (3 if lo < 0 else 0)                                  # lo < 0: ids outside [0, E) among them
+    idx = g.integers(lo, hi, size=(L, T, k)).astype(np.int32)
+    idx[:, : T // 3][idx[:, : T // 3] % 5 == 1] = E - 1            # uneven groups, more so early in the layer
+    need = B.group_workspace_bytes(L, T, k, E)
+    assert need > 0
+    got = _check_group(idx, E)
+    assert (int(got.n_invalid.sum()) > 0) == (lo < 0)
+
+
 def test_group_with_invalid_ids_and_repeats():
     g = np.random.default_rng(5)
     idx = g.integers(-3, 70, size=(2, 3000, 6)).astype(np.int32)     # ids outside [0, 64) on purpose
