@@ -98,7 +98,8 @@ __global__ __launch_bounds__(256) void group_scan_parts_kernel(int E, int P, int
 // ---------------------------------------------------------------------------
 static constexpr int FUSED_REGS = 32;                               // most positions per lane and sub-span (kept in registers)
 static constexpr int FUSED_MAX_ITEMS = 16 * 64 * FUSED_REGS;        // 32768 per part: positions must also fit 16 bits
-static constexpr size_t FUSED_MAX_LDS = 160 * 1024 - 512;           // per workgroup on gfx950, less the static part
+static constexpr int COLSUM_INTS = 1028;                            // partial column sums: at most max(1024, E + 1) of them
+static constexpr size_t FUSED_MAX_LDS = 160 * 1024 - 512 - 8 * COLSUM_INTS;   // per workgroup on gfx950, less the static part
 
 // The lanes of the wave that hold the same id as this one (valid lanes only; ids below 2^nbits2, nbits2 even).
 // Per id bit: one ballot, and every lane keeps the lanes whose bit equals its own.
@@ -128,6 +129,7 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 16 && REGS <= 8) ? 8 : WAVES 
     constexpr int THREADS = WAVES * 64;
     extern __shared__ int32_t smem[];
     __shared__ int32_t wave_tot[WAVES][3];
+    __shared__ int32_t colsum[PRE ? 2 * COLSUM_INTS : 1];
     const int layer = blockIdx.y, part = blockIdx.x;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int EP = E + 1;
@@ -138,11 +140,11 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 16 && REGS <= 8) ? 8 : WAVES 
     int32_t* list = gb + E;                                // [sub * WAVES]
     const int32_t* src = idx + (long long)layer * n;
     int32_t* dst = token_pos + (long long)layer * n;
-    for (int i = tid; i < (split ? 2 : 1) * WAVES * EP; i += THREADS) smem[i] = 0;
-    __syncthreads();
 
-    // whole layer, counted by wave shares (skipped when the workgroup owns the whole layer)
+    // whole layer, counted by wave shares (skipped when the workgroup owns the whole layer or has the parts' counts)
     if (split) {
+        for (int i = tid; i < 2 * WAVES * EP; i += THREADS) smem[i] = 0;
+        __syncthreads();
         int32_t* mineA = lhA + wave * EP;
         const int spanA = sub * P, firstA = wave * spanA;
         constexpr int NB = 8;                               // loads in flight
@@ -173,6 +175,37 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 16 && REGS <= 8) ? 8 : WAVES 
         const int p = first + 64 * j + lane;
         ev[j] = (64 * j < sub && p < n) ? src[p] : -1;
     }
+    // the parts' counts (PRE), summed by columns while the ids arrive: thread (r, e) takes the rows r, r + R, ...
+    // of column e (column E: the ids outside [0, E)); the R partial sums of a column meet in LDS.  Rows already
+    // turned into running sums need no adding up: row `part` and the totals' row are copied.
+    int col_groups = 1;
+    if (PRE) {
+        const int32_t* ph = part_hist + (long long)layer * (P + 1) * EP;
+        if (scanned) {
+            for (int e = tid; e < EP; e += THREADS) {
+                colsum[e] = ph[(long long)P * EP + e];
+                colsum[EP + e] = ph[(long long)part * EP + e];
+            }
+        } else {
+            col_groups = THREADS > EP ? THREADS / EP : 1;
+            for (int it = tid; it < col_groups * EP; it += THREADS) {
+                const int r = it / EP, e = it - r * EP;
+                int all = 0, bef = 0;
+#pragma unroll 8
+                for (int q = r; q < P; q += col_groups) {
+                    const int c = ph[(long long)q * EP + e];
+                    if (q < part) bef += c;
+                    all += c;
+                }
+                colsum[r * EP + e] = all;
+                colsum[(col_groups + r) * EP + e] = bef;
+            }
+        }
+    }
+    if (!split) {                                           // histograms cleared while the loads are under way
+        for (int i = tid; i < WAVES * EP; i += THREADS) smem[i] = 0;
+        __syncthreads();
+    }
 #pragma unroll
     for (int j = 0; j < REGS; ++j) {
         const int p = first + 64 * j + lane;
@@ -186,14 +219,13 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 16 && REGS <= 8) ? 8 : WAVES 
     // with each wave's first slot.  Thread t owns expert t, so a scan over threads is a scan over experts.
     int cnt = 0, cnt_mine = 0, before = 0;
     const int e_own = tid;
-    const int32_t* ph = PRE ? part_hist + (long long)layer * (P + 1) * EP : nullptr;
+    int first_slot[WAVES];                                  // of wave w for this expert, relative to the expert's run
     if (e_own < E) {
         int run = 0;
-#pragma unroll 4
+#pragma unroll
         for (int w = 0; w < WAVES; ++w) {
-            const int c = lhB[w * EP + e_own];
-            lhB[w * EP + e_own] = run;
-            run += c;
+            first_slot[w] = run;
+            run += lhB[w * EP + e_own];
         }
         cnt_mine = run;
         cnt = run;
@@ -208,17 +240,10 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 16 && REGS <= 8) ? 8 : WAVES 
             }
         }
         if (PRE) {
-            if (scanned) {
-                before = ph[(long long)part * EP + e_own];
-                cnt = ph[(long long)P * EP + e_own];
-            } else {
-                cnt = 0;
-#pragma unroll 8
-                for (int q = 0; q < P; ++q) {
-                    const int c = ph[(long long)q * EP + e_own];
-                    if (q < part) before += c;
-                    cnt += c;
-                }
+            cnt = before = 0;
+            for (int r = 0; r < col_groups; ++r) {
+                cnt += colsum[r * EP + e_own];
+                before += colsum[(col_groups + r) * EP + e_own];
             }
         }
     }
@@ -241,8 +266,8 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 16 && REGS <= 8) ? 8 : WAVES 
     const int off_e = woff + incl - cnt, loc_e = woff_m + incl_m - cnt_mine, aoff = woff_a + incl_a - (cnt > 0);
     if (e_own < E) {
         gb[e_own] = off_e + before - loc_e;
-#pragma unroll 4
-        for (int w = 0; w < WAVES; ++w) lhB[w * EP + e_own] += loc_e;      // first local slot of wave w for this expert
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) lhB[w * EP + e_own] = first_slot[w] + loc_e;   // wave w's cursor for this expert
     }
     if (part == 0) {                                        // every part knows the layer's totals; one writes them
         int32_t* offs = offsets + (long long)layer * EP;
@@ -258,8 +283,7 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 16 && REGS <= 8) ? 8 : WAVES 
             n_active[layer] = total_a;
             int bad = 0;
             if (PRE) {
-                if (scanned) bad = ph[(long long)P * EP + E];
-                else for (int q = 0; q < P; ++q) bad += ph[(long long)q * EP + E];
+                for (int r = 0; r < col_groups; ++r) bad += colsum[r * EP + E];
             } else {
                 const int32_t* h = split ? lhA : lhB;
                 for (int w = 0; w < WAVES; ++w) bad += h[w * EP + E];
