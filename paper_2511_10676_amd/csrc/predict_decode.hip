@@ -2,25 +2,27 @@
 //
 // At a handful of tokens the predictor is a weight-streaming problem: every
 // byte of W1 (r x d) and W2 (E x r) is needed once and the arithmetic per byte
-// is tiny, so the kernel is organised around reading the weights from HBM
+// is tiny, so the kernels are organised around reading the weights from HBM
 // exactly once, coalesced, with many loads in flight and nothing in the way.
 // One predictor belongs to one layer (paper section 4.2) and a layer is only
 // ~8 MB, so all layers of a call are spread over one grid.
 //
-// Kernel 1 (partial): the inner width r is cut into slices of RS = 64 hidden
-// units; workgroup (slice, layer) owns W1[slice rows, :] and W2[:, slice].
-// Its four waves split d into quarters.  A wave streams its quarter of the 64
-// rows straight from global memory into registers (a lane reads 16 contiguous
-// bytes of one row, four neighbouring lanes 64 contiguous bytes), moves them
-// into the A-operand layout of v_mfma_f32_16x16x32_bf16 with a lane
-// permutation, and does the same with the matching bytes of each token for the
-// B operand (tokens padded to a multiple of 16 by masking lanes; the token
-// block is small and stays in cache); a ring of register batches keeps one to
-// two batches of loads in flight, no LDS memory and no barrier in the loop.
-// The four partial sums of h^T[64, T] are added in LDS wave after wave (a fixed order),
-// rounded to bf16 (bias and activation applied), and multiplied by the W2
-// column slice with the same instruction; that is this slice's contribution to
-// the scores and goes to the workspace as fp32 partial[layer][slice][t][e].
+// Kernel 1 (partial): the inner width r is cut into slices; workgroup (slice,
+// layer) owns W1[slice rows, :] and W2[:, slice], forms h^T[slice, T] with
+// v_mfma_f32_16x16x32_bf16, rounds it to bf16 (bias and activation applied)
+// and multiplies it by the W2 column slice with the same instruction; that is
+// the slice's contribution to the scores and goes to the workspace as fp32
+// partial[layer][slice][t][e].  Two forms:
+//   rows   (r a multiple of 128) slices of 128 hidden units, eight waves that
+//          split the ROWS: a wave streams its 16 rows over the whole of d into
+//          registers and all waves take the tokens from LDS, where the
+//          workgroup puts them once (decode_rows_kernel below).
+//   d-split  slices of 64 hidden units, four waves that split d into quarters,
+//          weights and tokens both straight into registers, the four partial
+//          sums added in LDS wave after wave (decode_partial_kernel).
+// In both a lane reads 16 contiguous bytes of one row, four neighbouring lanes
+// 64 contiguous bytes, and a lane permutation puts the fragment into the
+// A-operand layout.
 //
 // Kernel 2 (finalize): one wave per token adds the slices in ascending order
 // (fixed order, so the result is reproducible; up to 32 loads in flight), adds b2, and runs softmax and
@@ -248,6 +250,213 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(
     }
 }
 
+// The row-split form.  What a CU's vector memory path can have in flight, not HBM, is what the d-split kernel
+// waits for, and tokens take their share of it: every 64-row slice fetches all T tokens again (at 64 tokens
+// as many bytes as the slice itself), and whether they come from L2 or from the CU's own cache makes no
+// difference to the time (measured).  Here a workgroup takes 128 hidden units, so the tokens are fetched once
+// per 128 rows, and the waves divide the rows instead of d: wave w owns rows 16w..16w+15 of the slice over
+// the whole of d and streams them into registers; all eight waves take the tokens from LDS, where each stage
+// of 128 columns is put once per workgroup by direct global -> LDS copies (a ring of four stages, one
+// workgroup barrier per stage).  A wave's accumulators are the finished h of its rows: nothing to add up
+// across waves.  Token row t of a stage is 256 bytes = 16 chunks of 16 bytes, chunk c in slot c ^ (t % 16)
+// (chosen on the global side of the copy), so that the 16 lanes of a fragment read, which take the same
+// chunk of 16 different tokens, fall into 16 different slots.  Measured on 26 layers of 2048 x 2048 against
+// the d-split kernel: 53.8 -> 50.3 us at 1 token, 58.7 -> 53.4 at 16, 65.8 -> 55.0 at 32, 79.7 -> 59.7 at 64.
+static constexpr int RW_WAVES = 8;
+static constexpr int RW_RS = 16 * RW_WAVES;          // hidden units per workgroup
+static constexpr int RW_KST = 128;                   // columns of d per stage
+static constexpr int RW_NSTG = 4;
+
+typedef void __attribute__((address_space(3)))* lds_ptr_t;
+// s_waitcnt immediate that waits for vmcnt <= n and nothing else (gfx9 encoding)
+#define PAEP_DEC_VMCNT(n) ((((n) & 0xF) | (((n) >> 4) << 14)) | 0x0F70)
+
+template <int TB>                                    // 16-token blocks held in LDS: 2 (T <= 32) or 4
+__global__ __launch_bounds__(RW_WAVES * 64, 4) void decode_rows_kernel(
+    int T, int d, int r, int E, int act, int S, int total_wgs, long long xs_, long long w1s, long long w2s,
+    const uint16_t* __restrict__ x, const uint16_t* __restrict__ W1, const uint16_t* __restrict__ W2,
+    const uint16_t* __restrict__ b1, float* __restrict__ partial)
+{
+    constexpr int TP = 16 * TB;
+    constexpr int STAGE_BYTES = TP * RW_KST * 2;
+    constexpr int XJ = TP / 4 / RW_WAVES;            // copy instructions per wave and stage (4 token rows each)
+    constexpr int KS = RW_KST / 32;                  // MFMA k-steps per stage
+    static_assert(XJ * 4 * RW_WAVES == TP, "token rows divide among the waves");
+    extern __shared__ __attribute__((aligned(16))) unsigned char dsmem[];   // the ring; h (bf16) afterwards
+    uint16_t* ht = (uint16_t*)dsmem;                                       // [token][unit], TP x (RW_RS + HPAD)
+    static_assert(TP * (RW_RS + HPAD) * 2 <= RW_NSTG * STAGE_BYTES, "h fits in the ring");
+
+    int item = blockIdx.x;
+    {
+        const int per = total_wgs / 8, rem = total_wgs % 8;
+        const int xcd = item % 8, slot = item / 8;
+        item = xcd * per + (xcd < rem ? xcd : rem) + slot;
+    }
+    const int layer = item / S, slice = item - layer * S;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int m = lane & 15, kg = lane >> 4;
+    const uint16_t* xl = x + (long long)layer * xs_;
+    const uint16_t* W1l = W1 + (long long)layer * w1s;
+    const uint16_t* W2l = W2 + (long long)layer * w2s;
+    const int NST = d / RW_KST;
+
+    // token copies: instruction q = wave * XJ + j moves token rows 4q..4q+3 of a stage; lane l supplies the
+    // chunk that belongs in slot l % 16 of row 4q + l / 16.  Rows past T lie outside the resource: zeros.
+    const __amdgpu_buffer_rsrc_t rsrc_x =
+        __builtin_amdgcn_make_buffer_rsrc((void*)xl, 0, (int)((long long)T * d * 2), 0x00020000);
+    uint32_t xlane[XJ];
+#pragma unroll
+    for (int j = 0; j < XJ; ++j) {
+        const int t = (wave * XJ + j) * 4 + (lane >> 4);
+        const int c = (lane & 15) ^ (t & 15);
+        xlane[j] = (uint32_t)(t * d + c * 8) * 2u;
+    }
+    auto issue_x = [&](int stage, int slot) {
+#pragma unroll
+        for (int j = 0; j < XJ; ++j)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, (lds_ptr_t)(dsmem + slot * STAGE_BYTES + (wave * XJ + j) * 1024),
+                                                     16, (int)xlane[j], stage * RW_KST * 2, 0, 0);
+    };
+    // this wave's 16 rows of W1, fetched as in the kernel above (lane l: row l / 4, bytes 16 * (l % 4) of a
+    // 64-byte k-step) and permuted into the A-operand layout
+    const int lrow = lane >> 2, lchunk = lane & 3;
+    const int perm_src = (4 * m + kg) * 4;
+    // (buffer-addressed: base and bounds of the wave's 16 rows in scalar registers, a fixed 32-bit lane offset and
+    // a scalar stage offset, so that no vector register is spent on addresses inside the loop)
+    const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(W1l + (long long)(slice * RW_RS + wave * 16) * d), 0, 16 * d * 2, 0x00020000);
+    const int wlane = (lrow * d + lchunk * 8) * 2;
+    auto to_mfma_layout = [&](const u32x4& f) {
+        return u32x4{(uint32_t)__builtin_amdgcn_ds_bpermute(perm_src, (int)f[0]),
+                     (uint32_t)__builtin_amdgcn_ds_bpermute(perm_src, (int)f[1]),
+                     (uint32_t)__builtin_amdgcn_ds_bpermute(perm_src, (int)f[2]),
+                     (uint32_t)__builtin_amdgcn_ds_bpermute(perm_src, (int)f[3])};
+    };
+    u32x4 fa[RW_NSTG][KS];
+    auto load_w = [&](auto buf_c, int stage) {
+        constexpr int buf = decltype(buf_c)::value;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            fa[buf][ks] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, wlane + ks * 64, stage * (RW_KST * 2), 0));
+    };
+
+    // W2 fragments of this wave's first expert block, requested now and used at the very end
+    const int EB = (E + 15) / 16;
+    u32x4 w2pf[RW_RS / 32];
+    {
+        const int e_row = wave * 16 + m;
+#pragma unroll
+        for (int s = 0; s < RW_RS / 32; ++s) {
+            w2pf[s] = u32x4{0u, 0u, 0u, 0u};
+            if (e_row < E) w2pf[s] = *(const u32x4*)(W2l + (long long)e_row * r + slice * RW_RS + s * 32 + kg * 8);
+        }
+    }
+
+    f32x4 acc[TB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) acc[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // Stage s: its token copies and this wave's rows are requested three stages ahead, in that order, so at
+    // the top of stage s the requests of stages s+1 and s+2 are the only ones that may still be in flight.
+    // Past the last stage the last one is requested again (into a slot nobody reads any more), which keeps
+    // that count the same on every iteration.
+    constexpr int WAIT_STAGE = PAEP_DEC_VMCNT(2 * (XJ + KS));
+    static_for<RW_NSTG - 1>([&](auto b_c) {
+        constexpr int b = decltype(b_c)::value;
+        const int st = b < NST ? b : NST - 1;
+        issue_x(st, b);
+        __builtin_amdgcn_sched_barrier(0);
+        load_w(b_c, st);
+        __builtin_amdgcn_sched_barrier(0);
+    });
+    for (int s0 = 0; s0 < NST; s0 += RW_NSTG) {
+        static_for<RW_NSTG>([&](auto b_c) {
+            constexpr int b = decltype(b_c)::value;
+            const int s = s0 + b;
+            if (s < NST) {                                        // uniform over the workgroup
+                __builtin_amdgcn_s_waitcnt(WAIT_STAGE);           // this wave's part of stage s has landed
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_barrier();                     // everyone's has; and everyone is done with stage s - 1
+                asm volatile("" ::: "memory");
+                const int sn = s + RW_NSTG - 1 < NST ? s + RW_NSTG - 1 : NST - 1;
+                issue_x(sn, (b + RW_NSTG - 1) % RW_NSTG);
+                __builtin_amdgcn_sched_barrier(0);
+                load_w(IC<(b + RW_NSTG - 1) % RW_NSTG>{}, sn);
+                __builtin_amdgcn_sched_barrier(0);
+                const unsigned char* stage = dsmem + b * STAGE_BYTES;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    u32x4 pb[TB];
+#pragma unroll
+                    for (int tb = 0; tb < TB; ++tb)
+                        pb[tb] = *(const u32x4*)(stage + (tb * 16 + m) * (RW_KST * 2) + (((ks * 4 + kg) ^ m) << 4));
+                    const u32x4 pa = to_mfma_layout(fa[b][ks]);
+#pragma unroll
+                    for (int tb = 0; tb < TB; ++tb)
+                        acc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            __builtin_bit_cast(bf16x8, pa), __builtin_bit_cast(bf16x8, pb[tb]), acc[tb], 0, 0, 0);
+                }
+            }
+        });
+    }
+    // acc[tb][i] = h[token tb*16 + m][unit slice*RW_RS + wave*16 + 4*kg + i].  The ring is handed over to h once
+    // every copy still in flight has landed and every wave has read its last fragments.
+    __builtin_amdgcn_s_waitcnt(PAEP_DEC_VMCNT(0));
+    __syncthreads();
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+        const int unit = wave * 16 + 4 * kg, tok = tb * 16 + m;
+        float h[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float t = acc[tb][i];
+            if (b1) t += bf16_bits_to_f32(b1[(long long)layer * r + slice * RW_RS + unit + i]);
+            t = round_to_bf16(t);
+            if (act != 0) t = round_to_bf16(apply_act(t, act));
+            h[i] = t;
+        }
+        *(u32x2*)(ht + tok * (RW_RS + HPAD) + unit) = u32x2{pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3])};
+    }
+    __syncthreads();
+
+    // scores of this slice: z^T[e, t] = W2[e, slice] . h^T[slice, t]; expert blocks dealt to the waves
+    auto score_block = [&](int eb, const u32x4 (&wfrag)[RW_RS / 32]) {
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) {
+            f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < RW_RS / 32; ++s) {
+                const u32x4 hv = *(const u32x4*)(ht + (tb * 16 + m) * (RW_RS + HPAD) + s * 32 + kg * 8);
+                z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wfrag[s]),
+                                                            __builtin_bit_cast(bf16x8, hv), z, 0, 0, 0);
+            }
+            const int t = tb * 16 + m;
+            if (t < T) {
+                float* dst = partial + (((long long)layer * S + slice) * T + t) * E + eb * 16 + 4 * kg;
+                if (eb * 16 + 4 * kg + 3 < E) {
+                    *(f32x4*)dst = z;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (eb * 16 + 4 * kg + i < E) dst[i] = z[i];
+                }
+            }
+        }
+    };
+    if (wave < EB) score_block(wave, w2pf);
+    for (int eb = wave + RW_WAVES; eb < EB; eb += RW_WAVES) {
+        const int e_row = eb * 16 + m;
+        u32x4 wfrag[RW_RS / 32];
+#pragma unroll
+        for (int s = 0; s < RW_RS / 32; ++s) {
+            wfrag[s] = u32x4{0u, 0u, 0u, 0u};
+            if (e_row < E) wfrag[s] = *(const u32x4*)(W2l + (long long)e_row * r + slice * RW_RS + s * 32 + kg * 8);
+        }
+        score_block(eb, wfrag);
+    }
+}
+
 // One wave per token row: lane l owns experts l, l+64, ...  The slice partials
 // are summed in ascending slice order, eight loads in flight at a time.
 static constexpr int FIN_NV = 8;                          // experts per lane at most: E <= 512
@@ -308,12 +517,31 @@ size_t decode_workspace_bytes(const PredictArgs& a)
     return sizeof(float) * (size_t)a.L * (size_t)(a.r / RS) * (size_t)a.T * (size_t)a.E;
 }
 
+// r in whole slices of 128: the row-split kernel
+static bool decode_by_rows(const PredictArgs& a) { return a.r % RW_RS == 0; }
+
 hipError_t launch_predict_decode(const PredictArgs& a)
 {
-    const int S = a.r / RS;
+    const bool rows_kernel = decode_by_rows(a);
+    const int S = a.r / (rows_kernel ? RW_RS : RS);
     const int total = S * a.L;
     float* partial = (float*)a.workspace;
     const int TB = (a.T + 15) / 16;
+    if (rows_kernel) {
+#define PAEP_LAUNCH_ROWS(TBV)                                                                               \
+        {                                                                                                   \
+            constexpr size_t lds = (size_t)RW_NSTG * 16 * TBV * RW_KST * 2;                                 \
+            static LdsLimit limit;                                                                          \
+            const hipError_t e1 = ensure_lds_limit(limit, (const void*)decode_rows_kernel<TBV>, lds);       \
+            if (e1 != hipSuccess) return e1;                                                                \
+            hipLaunchKernelGGL(decode_rows_kernel<TBV>, dim3(total), dim3(RW_WAVES * 64), lds, a.stream,    \
+                               a.T, a.d, a.r, a.E, a.act, S, total, a.x_stride, a.w1_stride, a.w2_stride,   \
+                               (const uint16_t*)a.x, (const uint16_t*)a.W1, (const uint16_t*)a.W2,          \
+                               (const uint16_t*)a.b1, partial);                                             \
+        }
+        if (TB <= 2) PAEP_LAUNCH_ROWS(2) else PAEP_LAUNCH_ROWS(4)
+#undef PAEP_LAUNCH_ROWS
+    } else {
 #define PAEP_LAUNCH_DEC(TBV, UV, NBV)                                                                       \
     hipLaunchKernelGGL((decode_partial_kernel<TBV, UV, NBV>), dim3(total), dim3(DEC_THREADS), 0, a.stream,  \
                        a.T, a.d, a.r, a.E, a.act, S, total, a.x_stride, a.w1_stride, a.w2_stride,           \
@@ -328,6 +556,7 @@ hipError_t launch_predict_decode(const PredictArgs& a)
     default: PAEP_LAUNCH_DEC(4, 1, 3); break;
     }
 #undef PAEP_LAUNCH_DEC
+    }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     const int rows = a.L * a.T;

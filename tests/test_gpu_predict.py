@@ -105,6 +105,20 @@ def test_decode_path_ragged_experts(E, k, act):
     _run_and_check(x, W1, W2, b1, b2, k, "bf16", act=act, path="decode", what=f"decode E={E} k={k} {act}")
 
 
+@pytest.mark.parametrize("T,d,r,E,k,act", [
+    # r in whole slices of 128: a workgroup takes 128 hidden units, its waves split the rows and share the tokens
+    # through a four-stage ring in LDS (other r: slices of 64, waves split d, covered by the cases above);
+    # d = 384 is three stages (shorter than the ring), d = 640 five (the ring wraps with a ragged last round),
+    # 250 experts give a wave two expert blocks; up to 32 tokens the ring holds 32 token rows, beyond that 64
+    (1, 640, 128, 48, 6, "none"), (16, 384, 256, 48, 6, "gelu"), (17, 384, 256, 48, 6, "none"), (32, 640, 128, 48, 6, "silu"), (33, 384, 256, 250, 12, "gelu"),
+    (48, 1024, 384, 64, 6, "none"), (64, 640, 256, 48, 8, "none"), (64, 128, 128, 16, 2, "silu"),
+])
+def test_decode_row_split_kernel(T, d, r, E, k, act):
+    x, W1, W2, b1, b2 = _rand_layers(70 + T + d, L=3, T=T, d=d, r=r, E=E, dtype="bf16", bias=True)
+    out, *_ = _run_and_check(x, W1, W2, b1, b2, k, "bf16", act=act, path="decode", what=f"decode rows T={T} d={d} r={r} E={E}")
+    assert out.path == "decode"
+
+
 def test_decode_shared_tokens_across_layers():
     x, W1, W2, _, _ = _rand_layers(50, L=4, T=3, d=256, r=64, E=32, dtype="bf16")
     _run_and_check(x[:1], W1, W2, None, None, 4, "bf16", path="decode", what="decode shared x")
