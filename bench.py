@@ -235,7 +235,8 @@ class Runner:
         self.entropy0 = round(float(prof.entropy[0]), 4)
         return {"T": T, "k_pred": self.k_pred, "path": self.path,
                 "launch": (f"{self.plan.tile} tiles, {self.plan.groups} workgroup(s) per token tile"
-                           if self.path == "prefill" else "r in slices of 64 per workgroup + finalize"),
+                           if self.path == "prefill" else
+                           f"r in slices of {128 if w.r % 128 == 0 else 64} per workgroup + finalize"),
                 "ms_per_step": round(ms_step, 4),
                 "value": round(T * w.L / (ms_step * 1e-3), 1), "roofline": roof,
                 "score_layer0": self.cnts[self.last][0].cpu().numpy().tolist(), "weight_banks": self.n_banks,

@@ -256,16 +256,17 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(
 // difference to the time (measured).  Here a workgroup takes 128 hidden units, so the tokens are fetched once
 // per 128 rows, and the waves divide the rows instead of d: wave w owns rows 16w..16w+15 of the slice over
 // the whole of d and streams them into registers; all eight waves take the tokens from LDS, where each stage
-// of 128 columns is put once per workgroup by direct global -> LDS copies (a ring of four stages, one
-// workgroup barrier per stage).  A wave's accumulators are the finished h of its rows: nothing to add up
+// of 128 columns is put once per workgroup by direct global -> LDS copies (two stages in turn, one workgroup
+// barrier per stage; with 16 waves per CU one stage of requests per wave already over-fills the memory
+// pipeline, and deeper rings measured slower).  A wave's accumulators are the finished h of its rows: nothing to add up
 // across waves.  Token row t of a stage is 256 bytes = 16 chunks of 16 bytes, chunk c in slot c ^ (t % 16)
 // (chosen on the global side of the copy), so that the 16 lanes of a fragment read, which take the same
 // chunk of 16 different tokens, fall into 16 different slots.  Measured on 26 layers of 2048 x 2048 against
-// the d-split kernel: 53.8 -> 50.3 us at 1 token, 58.7 -> 53.4 at 16, 65.8 -> 55.0 at 32, 79.7 -> 59.7 at 64.
+// the d-split kernel: 53.8 -> 49.8 us at 1 token, 58.7 -> 51.2 at 16, 79.7 -> 57.6 at 64.
 static constexpr int RW_WAVES = 8;
 static constexpr int RW_RS = 16 * RW_WAVES;          // hidden units per workgroup
 static constexpr int RW_KST = 128;                   // columns of d per stage
-static constexpr int RW_NSTG = 4;
+static constexpr int RW_NSTG = 2;                  // stages in the ring (deeper rings were slower: 4 stages +3 %)
 
 typedef void __attribute__((address_space(3)))* lds_ptr_t;
 // s_waitcnt immediate that waits for vmcnt <= n and nothing else (gfx9 encoding)
@@ -357,14 +358,22 @@ __global__ __launch_bounds__(RW_WAVES * 64, 4) void decode_rows_kernel(
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) acc[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // Stage s: its token copies and this wave's rows are requested three stages ahead, in that order, so at
-    // the top of stage s the requests of stages s+1 and s+2 are the only ones that may still be in flight.
-    // Past the last stage the last one is requested again (into a slot nobody reads any more), which keeps
-    // that count the same on every iteration.
-    constexpr int WAIT_STAGE = PAEP_DEC_VMCNT(2 * (XJ + KS));
+    // Stage s: its token copies and this wave's rows are requested RW_NSTG - 1 stages ahead, in that order, so
+    // at the top of stage s only the requests of the RW_NSTG - 2 stages after it may still be in flight.  Past
+    // the last stage the last one is requested again (into a slot nobody reads any more), which keeps that
+    // count the same on every iteration.
+    constexpr int WAIT_STAGE = PAEP_DEC_VMCNT((RW_NSTG - 2) * (XJ + KS));
+    // Workgroups start at different columns and wrap around (the s-th stage a workgroup works on is columns
+    // 128 * ((s + item) % NST) ..): all waves of the chip advance at about the same pace, and with a common
+    // starting column the addresses in flight at any moment would differ only in bits 12 and up -- rows are a
+    // power of two apart -- which lands them on a few memory channels for some placements of the weights
+    // (measured: 58 us against 48 us for one of four identically shaped banks; the same 48 us for all four with
+    // the rotation).  The order in which a workgroup adds up d is fixed by its position in the grid.
+    const int rot = item % NST;
+    auto column_stage = [&](int s) { return s + rot < NST ? s + rot : s + rot - NST; };
     static_for<RW_NSTG - 1>([&](auto b_c) {
         constexpr int b = decltype(b_c)::value;
-        const int st = b < NST ? b : NST - 1;
+        const int st = column_stage(b < NST ? b : NST - 1);
         issue_x(st, b);
         __builtin_amdgcn_sched_barrier(0);
         load_w(b_c, st);
@@ -379,7 +388,7 @@ __global__ __launch_bounds__(RW_WAVES * 64, 4) void decode_rows_kernel(
                 asm volatile("" ::: "memory");
                 __builtin_amdgcn_s_barrier();                     // everyone's has; and everyone is done with stage s - 1
                 asm volatile("" ::: "memory");
-                const int sn = s + RW_NSTG - 1 < NST ? s + RW_NSTG - 1 : NST - 1;
+                const int sn = column_stage(s + RW_NSTG - 1 < NST ? s + RW_NSTG - 1 : NST - 1);
                 issue_x(sn, (b + RW_NSTG - 1) % RW_NSTG);
                 __builtin_amdgcn_sched_barrier(0);
                 load_w(IC<(b + RW_NSTG - 1) % RW_NSTG>{}, sn);

@@ -107,9 +107,9 @@ def test_decode_path_ragged_experts(E, k, act):
 
 @pytest.mark.parametrize("T,d,r,E,k,act", [
     # r in whole slices of 128: a workgroup takes 128 hidden units, its waves split the rows and share the tokens
-    # through a four-stage ring in LDS (other r: slices of 64, waves split d, covered by the cases above);
-    # d = 384 is three stages (shorter than the ring), d = 640 five (the ring wraps with a ragged last round),
-    # 250 experts give a wave two expert blocks; up to 32 tokens the ring holds 32 token rows, beyond that 64
+    # through two LDS stages of 128 columns used in turn (other r: slices of 64, waves split d, covered by the
+    # cases above); d = 128 is a single stage, d = 384 and 640 an odd number of them, 250 experts give a wave two
+    # expert blocks; up to 32 tokens a stage holds 32 token rows, beyond that 64
     (1, 640, 128, 48, 6, "none"), (16, 384, 256, 48, 6, "gelu"), (17, 384, 256, 48, 6, "none"), (32, 640, 128, 48, 6, "silu"), (33, 384, 256, 250, 12, "gelu"),
     (48, 1024, 384, 64, 6, "none"), (64, 640, 256, 48, 8, "none"), (64, 128, 128, 16, 2, "silu"),
 ])
