@@ -105,16 +105,18 @@ def test_decode_path_ragged_experts(E, k, act):
     _run_and_check(x, W1, W2, b1, b2, k, "bf16", act=act, path="decode", what=f"decode E={E} k={k} {act}")
 
 
-@pytest.mark.parametrize("T,d,r,E,k,act", [
-    # r in whole slices of 128: a workgroup takes 128 hidden units, its waves split the rows and share the tokens
-    # through two LDS stages of 128 columns used in turn (other r: slices of 64, waves split d, covered by the
-    # cases above); d = 128 is a single stage, d = 384 and 640 an odd number of them, 250 experts give a wave two
-    # expert blocks; up to 32 tokens a stage holds 32 token rows, beyond that 64
-    (1, 640, 128, 48, 6, "none"), (16, 384, 256, 48, 6, "gelu"), (17, 384, 256, 48, 6, "none"), (32, 640, 128, 48, 6, "silu"), (33, 384, 256, 250, 12, "gelu"),
-    (48, 1024, 384, 64, 6, "none"), (64, 640, 256, 48, 8, "none"), (64, 128, 128, 16, 2, "silu"),
+@pytest.mark.parametrize("T,d,r,E,k,act,L", [
+    # r in whole slices of 128 and more than 16 tokens (or at least 384 slices in the call): a workgroup takes 128
+    # hidden units, its waves split the rows and share the tokens through two LDS stages of 128 columns used in
+    # turn (otherwise: slices of 64, waves split d, covered by the cases above); d = 128 is a single stage,
+    # d = 384 and 640 an odd number of them, 250 experts give a wave two expert blocks; up to 32 tokens a stage
+    # holds 32 token rows, beyond that 64
+    (1, 256, 1024, 48, 6, "none", 48), (16, 384, 512, 48, 6, "gelu", 96), (17, 384, 256, 48, 6, "none", 3),
+    (32, 640, 128, 48, 6, "silu", 3), (33, 384, 256, 250, 12, "gelu", 3), (48, 1024, 384, 64, 6, "none", 3),
+    (64, 640, 256, 48, 8, "none", 3), (64, 128, 128, 16, 2, "silu", 3),
 ])
-def test_decode_row_split_kernel(T, d, r, E, k, act):
-    x, W1, W2, b1, b2 = _rand_layers(70 + T + d, L=3, T=T, d=d, r=r, E=E, dtype="bf16", bias=True)
+def test_decode_row_split_kernel(T, d, r, E, k, act, L):
+    x, W1, W2, b1, b2 = _rand_layers(70 + T + d, L=L, T=T, d=d, r=r, E=E, dtype="bf16", bias=True)
     out, *_ = _run_and_check(x, W1, W2, b1, b2, k, "bf16", act=act, path="decode", what=f"decode rows T={T} d={d} r={r} E={E}")
     assert out.path == "decode"
 
