@@ -256,9 +256,10 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(
 // difference to the time (measured).  Here a workgroup takes 128 hidden units, so the tokens are fetched once
 // per 128 rows, and the waves divide the rows instead of d: wave w owns rows 16w..16w+15 of the slice over
 // the whole of d and streams them into registers; all eight waves take the tokens from LDS, where each stage
-// of 128 columns is put once per workgroup by direct global -> LDS copies (two stages in turn, one workgroup
-// barrier per stage; with 16 waves per CU one stage of requests per wave already over-fills the memory
-// pipeline, and deeper rings measured slower).  A wave's accumulators are the finished h of its rows: nothing to add up
+// of 128 columns is put once per workgroup by direct global -> LDS copies (a ring of two or three stages, one
+// workgroup barrier per stage: with two workgroups on a CU one stage of requests ahead per wave already
+// over-fills the memory pipeline and deeper rings measured 2-3 % slower; with one workgroup per CU two
+// stages ahead are 5-9 % faster).  A wave's accumulators are the finished h of its rows: nothing to add up
 // across waves.  Token row t of a stage is 256 bytes = 16 chunks of 16 bytes, chunk c in slot c ^ (t % 16)
 // (chosen on the global side of the copy), so that the 16 lanes of a fragment read, which take the same
 // chunk of 16 different tokens, fall into 16 different slots.  Measured on 26 layers of 2048 x 2048 against
@@ -266,13 +267,13 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(
 static constexpr int RW_WAVES = 8;
 static constexpr int RW_RS = 16 * RW_WAVES;          // hidden units per workgroup
 static constexpr int RW_KST = 128;                   // columns of d per stage
-static constexpr int RW_NSTG = 2;                  // stages in the ring (deeper rings were slower: 4 stages +3 %)
 
 typedef void __attribute__((address_space(3)))* lds_ptr_t;
 // s_waitcnt immediate that waits for vmcnt <= n and nothing else (gfx9 encoding)
 #define PAEP_DEC_VMCNT(n) ((((n) & 0xF) | (((n) >> 4) << 14)) | 0x0F70)
 
-template <int TB>                                    // 16-token blocks held in LDS: 2 (T <= 32) or 4
+// TB: 16-token blocks held in LDS, 2 (T <= 32) or 4; RW_NSTG: stages in the ring, 2 or 3
+template <int TB, int RW_NSTG>
 __global__ __launch_bounds__(RW_WAVES * 64, 4) void decode_rows_kernel(
     int T, int d, int r, int E, int act, int S, int total_wgs, long long xs_, long long w1s, long long w2s,
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ W1, const uint16_t* __restrict__ W2,
@@ -526,14 +527,10 @@ size_t decode_workspace_bytes(const PredictArgs& a)
     return sizeof(float) * (size_t)a.L * (size_t)(a.r / RS) * (size_t)a.T * (size_t)a.E;
 }
 
-// r in whole slices of 128: the row-split kernel, unless there are at most 16 tokens (whose fetches weigh
-// little) and too few 128-row slices to keep the CUs' memory pipelines full (measured at 1 token: 256 slices
-// 60.0 us against 57.2 us for the d-split kernel's 512 workgroups; 416 slices 49.2 against 53.8; 768 equal)
-static bool decode_by_rows(const PredictArgs& a)
-{
-    if (a.r % RW_RS != 0) return false;
-    return a.T > 16 || (long long)(a.r / RW_RS) * a.L >= 384;
-}
+// r in whole slices of 128: the row-split kernel (measured against the d-split kernel at 1 token: 26 layers of
+// 2048 x 2048 49.2 against 53.8 us, 32 layers of 1024 x 4096 56.0 against 57.5, 48 layers of 2048 x 2048 equal;
+// at 32 and 64 tokens 10-27 % faster)
+static bool decode_by_rows(const PredictArgs& a) { return a.r % RW_RS == 0; }
 
 hipError_t launch_predict_decode(const PredictArgs& a)
 {
@@ -543,18 +540,21 @@ hipError_t launch_predict_decode(const PredictArgs& a)
     float* partial = (float*)a.workspace;
     const int TB = (a.T + 15) / 16;
     if (rows_kernel) {
-#define PAEP_LAUNCH_ROWS(TBV)                                                                               \
+#define PAEP_LAUNCH_ROWS(TBV, NSV)                                                                          \
         {                                                                                                   \
-            constexpr size_t lds = (size_t)RW_NSTG * 16 * TBV * RW_KST * 2;                                 \
+            constexpr size_t lds = (size_t)NSV * 16 * TBV * RW_KST * 2;                                     \
             static LdsLimit limit;                                                                          \
-            const hipError_t e1 = ensure_lds_limit(limit, (const void*)decode_rows_kernel<TBV>, lds);       \
+            const hipError_t e1 = ensure_lds_limit(limit, (const void*)decode_rows_kernel<TBV, NSV>, lds);  \
             if (e1 != hipSuccess) return e1;                                                                \
-            hipLaunchKernelGGL(decode_rows_kernel<TBV>, dim3(total), dim3(RW_WAVES * 64), lds, a.stream,    \
+            hipLaunchKernelGGL((decode_rows_kernel<TBV, NSV>), dim3(total), dim3(RW_WAVES * 64), lds, a.stream, \
                                a.T, a.d, a.r, a.E, a.act, S, total, a.x_stride, a.w1_stride, a.w2_stride,   \
                                (const uint16_t*)a.x, (const uint16_t*)a.W1, (const uint16_t*)a.W2,          \
                                (const uint16_t*)a.b1, partial);                                             \
         }
-        if (TB <= 2) PAEP_LAUNCH_ROWS(2) else PAEP_LAUNCH_ROWS(4)
+        // fewer than one and a half workgroups per CU: a deeper ring
+        const bool deep = total < 384;
+        if (TB <= 2) { if (deep) PAEP_LAUNCH_ROWS(2, 3) else PAEP_LAUNCH_ROWS(2, 2) }
+        else         { if (deep) PAEP_LAUNCH_ROWS(4, 3) else PAEP_LAUNCH_ROWS(4, 2) }
 #undef PAEP_LAUNCH_ROWS
     } else {
 #define PAEP_LAUNCH_DEC(TBV, UV, NBV)                                                                       \

@@ -106,11 +106,11 @@ def test_decode_path_ragged_experts(E, k, act):
 
 
 @pytest.mark.parametrize("T,d,r,E,k,act,L", [
-    # r in whole slices of 128 and more than 16 tokens (or at least 384 slices in the call): a workgroup takes 128
-    # hidden units, its waves split the rows and share the tokens through two LDS stages of 128 columns used in
-    # turn (otherwise: slices of 64, waves split d, covered by the cases above); d = 128 is a single stage,
-    # d = 384 and 640 an odd number of them, 250 experts give a wave two expert blocks; up to 32 tokens a stage
-    # holds 32 token rows, beyond that 64
+    # r in whole slices of 128: a workgroup takes 128 hidden units, its waves split the rows and share the tokens
+    # through a ring of LDS stages of 128 columns (otherwise: slices of 64, waves split d, covered by the cases
+    # above).  The ring has three stages in calls of fewer than 384 slices (the cases with 3 layers) and two
+    # beyond (the first two cases); d = 128 is a single stage, d = 384 and 640 a ragged last round, 250 experts
+    # give a wave two expert blocks; up to 32 tokens a stage holds 32 token rows, beyond that 64
     (1, 256, 1024, 48, 6, "none", 48), (16, 384, 512, 48, 6, "gelu", 96), (17, 384, 256, 48, 6, "none", 3),
     (32, 640, 128, 48, 6, "silu", 3), (33, 384, 256, 250, 12, "gelu", 3), (48, 1024, 384, 64, 6, "none", 3),
     (64, 640, 256, 48, 8, "none", 3), (64, 128, 128, 16, 2, "silu", 3),
