@@ -48,8 +48,8 @@ TRAFFIC_BYTES = {
                                       ("qwen3_30b_a3b", 8192): 1.457e+10,
                                       ("phi_mini_moe", 8192): 4.91e+09,
                                       ("stress", 32768): 2.41e+11},
-    ("decode", "24359a7f2bdbb167"): {("deepseek_v2_lite", 1): 2.258e+08,
-                                     ("deepseek_v2_lite", 64): 2.586e+08},
+    ("decode", "d527a095cb363a51"): {("deepseek_v2_lite", 1): 2.259e+08,
+                                     ("deepseek_v2_lite", 64): 2.588e+08},
 }
 
 
