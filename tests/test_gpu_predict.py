@@ -124,6 +124,18 @@ def test_decode_row_split_kernel(T, d, r, E, k, act, L):
 def test_decode_shared_tokens_across_layers():
     x, W1, W2, _, _ = _rand_layers(50, L=4, T=3, d=256, r=64, E=32, dtype="bf16")
     _run_and_check(x[:1], W1, W2, None, None, 4, "bf16", path="decode", what="decode shared x")
+    # the same through the row-split kernel (r = 256), no biases, both token-block sizes
+    for T in (20, 50):
+        x, W1, W2, _, _ = _rand_layers(52 + T, L=4, T=T, d=256, r=256, E=32, dtype="bf16")
+        _run_and_check(x[:1], W1, W2, None, None, 4, "bf16", path="decode", what=f"decode rows shared x T={T}")
+
+
+def test_decode_row_split_many_experts_and_wide_k():
+    # 512 experts (eight per lane in the finalize kernel, four expert blocks per wave in the slices kernel) and k = 32
+    x, W1, W2, b1, b2 = _rand_layers(57, L=2, T=40, d=256, r=256, E=512, dtype="bf16", bias=True)
+    _run_and_check(x, W1, W2, b1, b2, 32, "bf16", act="silu", path="decode", what="decode rows E=512 k=32")
+    x, W1, W2, b1, b2 = _rand_layers(58, L=2, T=9, d=128, r=128, E=130, dtype="bf16", bias=True)
+    _run_and_check(x, W1, W2, b1, b2, 16, "bf16", path="decode", what="decode rows E=130 k=16")
 
 
 # ------------------------------------------------------------------ prefill path
